@@ -1,0 +1,180 @@
+/*
+ * flowspec.h — C ABI of the MI355X (gfx950) tree-verification stage library.
+ *
+ * One FlowSpec verification stage V_n (paper, Sec. III-A): a block of decoder layers of the base
+ * model run over one segment of the draft sequence S (draft-tree nodes in descending
+ * cumulative-score order, Sec. III-B) with tree attention against the stage's KV cache, followed
+ * — at the last stage — by next-token scores, acceptance with the continuous condition (Sec.
+ * III-C, Eq. 2) and — at every stage — pruning of the KV cache and of in-flight segments by the
+ * retain set I_retain (Sec. III-C).
+ *
+ * Conventions
+ *   - Every function returns 0 (FS_OK) or a negative error code; nothing is thrown.
+ *   - "device" pointers are HIP device memory owned by the caller (e.g. obtained from PyTorch);
+ *     "host" pointers are ordinary host memory.  The library allocates no device memory: all it
+ *     needs beyond the caller's tensors lives in the workspace passed to fs_stage_create, whose
+ *     size fs_stage_workspace_bytes reports.  The workspace holds a private, re-tiled copy of the
+ *     weights, so the caller's weight tensors may be released once fs_stage_create's stream work
+ *     has finished.
+ *   - All GPU work is enqueued on the caller's stream (hipStream_t passed as void*; NULL is the
+ *     default stream) and is asynchronous to the host.  Only fs_accept_result_to_host waits.
+ *   - A stage object is used by one stream at a time; calls on one stage that overlap in time race
+ *     on its workspace.
+ *   - Element type of weights, activations and KV cache is given by fs_stage_desc.dtype:
+ *     FS_F32 (float) or FS_BF16 (bfloat16).  Accumulation and the residual stream are fp32.
+ *   - S indices: node j of the current draft sequence lives at KV slot l_glo + j, where l_glo is
+ *     the global context offset (prompt + accepted tokens, Sec. III-C).
+ */
+#ifndef FLOWSPEC_H
+#define FLOWSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_OK 0
+#define FS_EINVAL (-1) /* null pointer, bad shape or size, unmet precondition */
+#define FS_ETOPO (-2)  /* parent array is not a topological order: needs parent[0] == -1 (verify) and -1 <= parent[i] < i */
+#define FS_ECAP (-3)   /* l_cache + l_s exceeds kv_capacity, tree larger than max_tree, segment longer than max_seg */
+#define FS_EDTYPE (-4) /* dtype is neither FS_F32 nor FS_BF16 */
+#define FS_EHIP (-5)   /* a HIP call failed; fs_last_hip_error() returns its hipError_t */
+#define FS_EWS (-6)    /* workspace missing, misaligned (256 B) or smaller than fs_stage_workspace_bytes */
+
+#define FS_F32 0
+#define FS_BF16 1
+
+#define FS_MAX_TREE 1024 /* largest draft tree (nodes of S) any entry point accepts */
+
+/* Shape of a stage (decoder form per Appendix A and the LLaMA2 / Qwen2 models of Sec. IV-A). */
+typedef struct {
+    int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn;
+    int vocab;       /* > 0: last stage with an LM head of that many rows; 0: no head */
+    int dtype;       /* FS_F32 | FS_BF16 */
+    float rms_eps;   /* RMSNorm epsilon */
+    float rope_theta;/* rotary base; element t pairs with t + head_dim/2, angle = pos * theta^(-2t/head_dim) */
+    int kv_capacity; /* slots per head of the KV cache the stage will be used with */
+    int max_tree;    /* largest T (<= FS_MAX_TREE) */
+    int max_seg;     /* largest segment length l_s (the paper's L_max) */
+} fs_stage_desc;
+
+/* One layer's tensors, device, row-major [out, in], element type desc.dtype.  Biases may be NULL. */
+typedef struct {
+    const void *rms_attn, *wq, *wk, *wv, *wo, *rms_ffn, *w_gate, *w_up, *w_down;
+    const void *bq, *bk, *bv;
+} fs_layer_weights;
+
+/* KV cache, device, element type desc.dtype.  Element (layer, kv, head, slot, t) is at
+ * base + layer*stride_layer + kv*stride_kv + head*stride_head + slot*stride_tok + t   (strides in elements,
+ * kv = 0 for K — stored after rotation — and 1 for V).  stride_tok must be a multiple of 8 (bf16) / 4 (f32)
+ * elements and base 16-byte aligned.  Slots [0, l_cache) are valid. */
+typedef struct {
+    void *base;
+    long long stride_layer, stride_kv, stride_head, stride_tok;
+} fs_kv_cache;
+
+typedef struct fs_stage fs_stage;
+
+/* Bytes of device workspace a stage of this shape needs (0 on a bad descriptor). */
+size_t fs_stage_workspace_bytes(const fs_stage_desc *desc);
+
+/*
+ * Create a stage: validates the shape, re-tiles the weights into the workspace (kernels on `stream`).
+ *   layers      host array [n_layers] of device pointers
+ *   final_norm  device [d_model], lm_head device [vocab, d_model]; both required iff desc->vocab > 0
+ *   workspace   device, 256-byte aligned, >= fs_stage_workspace_bytes(desc); owned by the caller and must
+ *               outlive the stage
+ * Errors: FS_EINVAL, FS_EDTYPE, FS_ECAP (max_tree > FS_MAX_TREE), FS_EWS, FS_EHIP.
+ */
+int fs_stage_create(const fs_stage_desc *desc, const fs_layer_weights *layers, const void *final_norm, const void *lm_head,
+                    void *workspace, size_t workspace_bytes, void *stream, fs_stage **out);
+int fs_stage_destroy(fs_stage *stage);
+
+/* hipError_t (as int) behind the most recent FS_EHIP on the calling thread, 0 if none. */
+int fs_last_hip_error(void);
+
+/*
+ * Verification-stage forward (Sec. III-A: "executing the corresponding forward pass during the verification
+ * of draft tokens"; a segment carries its tree position IDs and attention mask, both derived here from the
+ * parent array).  Runs the stage's layers over segment S[seg_off, seg_off + l_s):
+ *   per layer: RMSNorm -> Q/K/V projections (+bias) -> rotary embedding at position l_glo + depth(node) ->
+ *   K/V of row r stored at slot l_cache + r -> tree attention (row r sees every slot < l_glo and the draft
+ *   slots l_glo + j with j an ancestor-or-self of node seg_off + r) -> output projection + residual ->
+ *   RMSNorm -> SwiGLU feed-forward + residual.
+ *   hidden_in / hidden_out  device [l_s, d_model], may alias
+ *   parent                  HOST [seg_off + l_s], S order, parent[0] == -1 (further roots allowed: such a node
+ *                           sees the context and itself only); read before the call returns
+ * Precondition: l_cache == l_glo + seg_off.  l_s == 0 is a valid no-op.
+ * Errors: FS_EINVAL, FS_ETOPO, FS_ECAP, FS_EHIP.
+ */
+int fs_tree_verify_stage(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache, const void *hidden_in, int seg_off, int l_s,
+                         const int32_t *parent, void *hidden_out, void *stream);
+
+/*
+ * Last stage's verification output (Sec. III-A, continuous SD step: the next-token distribution sent to the
+ * draft stage): logits = RMSNorm_final(hidden) * E^T in fp32 and their per-row argmax (lowest index on ties).
+ *   hidden device [l_s, d_model]; logits device fp32 [l_s, vocab]; amax device int32 [l_s].
+ * Errors: FS_EINVAL (stage has no head, l_s > max_seg), FS_EHIP.
+ */
+int fs_tree_logits(fs_stage *stage, const void *hidden, int l_s, float *logits, int32_t *amax, void *stream);
+
+/* Acceptance result (Sec. III-C), device or host. */
+typedef struct {
+    int32_t n_acc;         /* |S_acc| = |I_acc|, counts the root x_new of the tree; 0 only if n_ver == 0 */
+    int32_t x_new;         /* newly sampled token (greedy: argmax at the last accepted node); -1 if n_ver == 0 */
+    int32_t n_new;         /* S index of the node with path(n_new) = S_acc || x_new, or -1 */
+    int32_t continuous;    /* continuous condition, Eq. 2 */
+    int32_t n_retain;      /* |I_retain| */
+    int32_t n_pr_verified; /* retained draft nodes that already have a verification output */
+} fs_accept_result;
+
+/*
+ * Greedy acceptance over the verified prefix [0, n_ver) of S (Sec. III-C: accepted tokens S_acc, x_new,
+ * continuous condition Eq. 2, retain set I_retain = I_acc U I_pr with n_new's subtree in original order).
+ *   logits  device fp32 [n_ver, vocab] or NULL; when given, amax[0, n_ver) is first recomputed from it
+ *   amax    device int32 [n_ver] (output when logits != NULL, input otherwise)
+ *   token, parent  device int32 [T], S order
+ *   res     device; retain device int32 [T]: I_acc ascending, then I_pr ascending
+ *   work    device int32 scratch, at least 2 * n_ver * FS_ARGMAX_CHUNKS entries when logits != NULL, else unused
+ * A node whose parent array entry breaks the topological order makes res->n_acc = -1 (nothing else is written).
+ * n_ver == 0: nothing accepted, everything retained.
+ * Errors: FS_EINVAL, FS_ECAP (T > FS_MAX_TREE), FS_EHIP.
+ */
+#define FS_ARGMAX_CHUNKS 64
+int fs_tree_accept(const float *logits, int32_t *amax, int vocab, const int32_t *token, const int32_t *parent, int T, int n_ver,
+                   fs_accept_result *res, int32_t *retain, int32_t *work, void *stream);
+
+/* Copies the result and the first n_retain entries of retain to the host and waits for the stream: the one
+ * synchronisation point of the path.  retain_host must hold T entries. */
+int fs_accept_result_to_host(const fs_accept_result *res_dev, const int32_t *retain_dev, int T, fs_accept_result *res_host,
+                             int32_t *retain_host, void *stream);
+
+/*
+ * KV-cache pruning (Sec. III-C, "KV cache pruning"): with I_incache = { i in I_retain : l_glo + i < l_cache },
+ * slot l_glo + j <- slot l_glo + I_incache[j] for every layer, K and V, every head; slots below l_glo are not
+ * touched.  Bit-exact copy, in place.
+ *   retain / res   either both device (straight from fs_tree_accept; counts are read on the device), or
+ *                  res == NULL and retain a HOST array with n_retain_host entries of which the first n_acc_host
+ *                  are accepted (the paper's case: the retain set arrives from the draft stage)
+ *   new_len        device int32 [2], optional: { l_glo + n_acc, l_glo + |I_incache| }
+ * Errors: FS_EINVAL, FS_ECAP, FS_EHIP.
+ */
+int fs_kv_compact(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache, const int32_t *retain, const fs_accept_result *res,
+                  int n_retain_host, int n_acc_host, int32_t *new_len, void *stream);
+
+/*
+ * Draft-segment pruning (Sec. III-C, "Draft segment pruning"): the in-flight segment holds S indices
+ * [off, off + l_s) with off = l_cache - l_glo; rows with off + r in I_retain are gathered, in order, into
+ * seg_out (must not overlap seg_in); *l_s_out = number kept.
+ *   seg_in / seg_out device [l_s, row_bytes]; row_bytes a multiple of 4
+ *   retain / res as in fs_kv_compact;  l_s_out device int32 [1]
+ */
+int fs_seg_prune(const void *seg_in, int l_s, size_t row_bytes, int off, const int32_t *retain, const fs_accept_result *res,
+                 int n_retain_host, void *seg_out, int32_t *l_s_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOWSPEC_H */

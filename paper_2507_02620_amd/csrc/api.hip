@@ -1,0 +1,426 @@
+// Host side of the C ABI declared in include/flowspec.h: validation, workspace layout, launch sequencing.
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/flowspec.h"
+#include "attention.hpp"
+#include "gemm.hpp"
+#include "tree.hpp"
+
+static thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                 \
+    do {                              \
+        hipError_t e__ = (expr);      \
+        if (e__ != hipSuccess) {      \
+            g_last_hip = (int)e__;    \
+            return FS_EHIP;           \
+        }                             \
+    } while (0)
+
+namespace {
+
+struct GemmPlan {
+    void* wp = nullptr;
+    float* bias = nullptr;
+    int N = 0, K = 0, nkt = 0, NT = 1, NW = 8, n_groups = 0;
+    size_t bytes() const { return (size_t)n_groups * nkt * NT * 1024; }
+};
+
+struct LayerPlan {
+    GemmPlan qkv, o, gu, down;
+};
+
+constexpr int kMaxSplits = 64;
+
+int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+// Tiles per group: the largest allowed NT that still leaves about two workgroups per compute unit;
+// segments longer than 16 rows prefer NT >= 2 so that activation re-reads through L2 stay below the weight stream.
+int choose_nt(int tiles, bool pair, int max_seg, const char* env) {
+    int nt = pair ? 2 : 1;
+    if (tiles / 4 >= 512) nt = 4;
+    else if (tiles / 2 >= 512) nt = 2;
+    if (max_seg > 16 && nt < 2 && tiles / 2 >= 160) nt = 2;
+    int o = env_int(env, 0);
+    if (o == 1 || o == 2 || o == 4) nt = (pair && o == 1) ? 2 : o;
+    return nt;
+}
+
+void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, const char* env_nt) {
+    const int KT = 64 / elem;  // 32 for bf16, 16 for f32
+    g.K = K;
+    g.nkt = (K + KT - 1) / KT;
+    g.NT = choose_nt(tiles, pair, max_seg, env_nt);
+    g.n_groups = (tiles + g.NT - 1) / g.NT;
+    g.NW = env_int("FLOWSPEC_NW", 8);
+    if (g.NW < 1 || g.NW > 8) g.NW = 8;
+    if (g.NW > g.nkt) g.NW = g.nkt;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    std::vector<LayerPlan> layers;
+    GemmPlan head;
+    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, total;
+};
+
+bool valid_desc(const fs_stage_desc* d, int* err) {
+    *err = FS_EINVAL;
+    if (!d) return false;
+    if (d->dtype != FS_F32 && d->dtype != FS_BF16) {
+        *err = FS_EDTYPE;
+        return false;
+    }
+    if (d->max_tree > FS_MAX_TREE) {
+        *err = FS_ECAP;
+        return false;
+    }
+    if (d->n_layers < 1 || d->d_model < 16 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 8 || d->vocab < 0) return false;
+    if (d->n_q_heads % d->n_kv_heads) return false;
+    if (d->head_dim != 64 && d->head_dim != 128) return false;
+    if (d->d_model % 16 || d->d_ffn % 8) return false;
+    if (d->kv_capacity < 1 || d->max_tree < 1 || d->max_seg < 1 || d->max_seg > FS_MAX_TREE) return false;
+    if (!(d->rms_eps >= 0.f) || !(d->rope_theta > 0.f)) return false;
+    return true;
+}
+
+void make_layout(const fs_stage_desc* d, Layout& L) {
+    const int elem = d->dtype == FS_F32 ? 4 : 2;
+    const int hd = d->head_dim, nq = d->n_q_heads * hd;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    L.layers.resize(d->n_layers);
+    for (int l = 0; l < d->n_layers; ++l) {
+        LayerPlan& p = L.layers[l];
+        const int qkv_tiles = (d->n_q_heads + 2 * d->n_kv_heads) * hd / 16;
+        plan_gemm(p.qkv, qkv_tiles, d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_QKV");
+        p.qkv.N = qkv_tiles * 16;
+        plan_gemm(p.o, d->d_model / 16, nq, elem, false, d->max_seg, "FLOWSPEC_NT_O");
+        p.o.N = d->d_model;
+        plan_gemm(p.gu, 2 * ((d->d_ffn + 15) / 16), d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_GU");
+        p.gu.N = d->d_ffn;
+        plan_gemm(p.down, d->d_model / 16, d->d_ffn, elem, false, d->max_seg, "FLOWSPEC_NT_DOWN");
+        p.down.N = d->d_model;
+        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) g->wp = (void*)take(g->bytes());
+        p.qkv.bias = (float*)take((size_t)p.qkv.n_groups * p.qkv.NT * 16 * sizeof(float));
+    }
+    if (d->vocab > 0) {
+        plan_gemm(L.head, (d->vocab + 15) / 16, d->d_model, elem, false, d->max_seg, "FLOWSPEC_NT_HEAD");
+        L.head.N = d->vocab;
+        L.head.wp = (void*)take(L.head.bytes());
+    }
+    const size_t M = (size_t)d->max_seg;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    const size_t Rpad = align_up((size_t)G * M, 16);
+    L.off_q = take(M * nq * elem);
+    L.off_o = take(M * nq * elem);
+    L.off_h = take(M * d->d_model * sizeof(float));
+    L.off_hb = take(M * d->d_model * elem);
+    L.off_act = take(M * d->d_ffn * elem);
+    L.off_anc = take(M * FS_ANC_WORDS * sizeof(uint64_t));
+    L.off_rope = take(M * (hd / 2) * sizeof(float2));
+    L.off_po = take((size_t)kMaxSplits * d->n_kv_heads * Rpad * hd * sizeof(float));
+    L.off_pml = take((size_t)kMaxSplits * d->n_kv_heads * Rpad * 2 * sizeof(float));
+    L.off_amw = take(M * FS_ARGMAX_CHUNKS * 2 * sizeof(int32_t));
+    L.total = off;
+}
+
+int valid_kv(const fs_stage_desc& d, const fs_kv_cache& kv) {
+    const int elem = d.dtype == FS_F32 ? 4 : 2, epf = 16 / elem;
+    if (!kv.base || ((uintptr_t)kv.base & 15)) return FS_EINVAL;
+    if (kv.stride_tok < d.head_dim || kv.stride_tok % epf || kv.stride_head % epf || kv.stride_kv % epf || kv.stride_layer % epf) return FS_EINVAL;
+    if (kv.stride_head < 0 || kv.stride_kv < 0 || kv.stride_layer < 0) return FS_EINVAL;
+    return FS_OK;
+}
+
+int fill_idx(IdxList& L, const int32_t* v, int n) {
+    if (n < 0 || n > 1024) return FS_ECAP;
+    L.n = n;
+    for (int i = 0; i < n; ++i) {
+        if (v[i] < -1 || v[i] > 1023) return FS_EINVAL;
+        L.v[i] = (short)v[i];
+    }
+    return FS_OK;
+}
+
+}  // namespace
+
+struct fs_stage {
+    fs_stage_desc d;
+    Layout L;
+    unsigned char* ws;
+    int elem;
+    template <typename P>
+    P* at(size_t off) const { return (P*)(ws + off); }
+};
+
+extern "C" {
+
+int fs_last_hip_error(void) { return g_last_hip; }
+
+size_t fs_stage_workspace_bytes(const fs_stage_desc* desc) {
+    int err;
+    if (!valid_desc(desc, &err)) return 0;
+    Layout L;
+    make_layout(desc, L);
+    return L.total;
+}
+
+int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, const void* final_norm, const void* lm_head, void* workspace,
+                    size_t workspace_bytes, void* stream, fs_stage** out) {
+    int err;
+    if (!out) return FS_EINVAL;
+    *out = nullptr;
+    if (!valid_desc(desc, &err)) return err;
+    if (!layers) return FS_EINVAL;
+    if (desc->vocab > 0 && (!final_norm || !lm_head)) return FS_EINVAL;
+    for (int l = 0; l < desc->n_layers; ++l) {
+        const fs_layer_weights& w = layers[l];
+        if (!w.rms_attn || !w.wq || !w.wk || !w.wv || !w.wo || !w.rms_ffn || !w.w_gate || !w.w_up || !w.w_down) return FS_EINVAL;
+    }
+    fs_stage* st = new (std::nothrow) fs_stage;
+    if (!st) return FS_EINVAL;
+    st->d = *desc;
+    st->elem = desc->dtype == FS_F32 ? 4 : 2;
+    make_layout(desc, st->L);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < st->L.total) {
+        delete st;
+        return FS_EWS;
+    }
+    st->ws = (unsigned char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    const int hd = desc->head_dim;
+    for (int l = 0; l < desc->n_layers; ++l) {
+        LayerPlan& p = st->L.layers[l];
+        const fs_layer_weights& w = layers[l];
+        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) g->wp = st->ws + (size_t)g->wp;
+        p.qkv.bias = (float*)(st->ws + (size_t)p.qkv.bias);
+        PackArgs a{};
+        a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.hd = hd;
+        // QKV (attention RMSNorm gain folded in)
+        a.kind = PACK_QKV; a.src0 = w.wq; a.src1 = w.wk; a.src2 = w.wv; a.gain = w.rms_attn; a.dst = p.qkv.wp;
+        a.N = p.qkv.N; a.K = p.qkv.K; a.nkt = p.qkv.nkt; a.NT = p.qkv.NT; a.n_groups = p.qkv.n_groups;
+        a.b0 = w.bq; a.b1 = w.bk; a.b2 = w.bv; a.bias_dst = p.qkv.bias;
+        launch_pack(desc->dtype, a, s);
+        if (!w.bq && !w.bk && !w.bv) p.qkv.bias = nullptr;  // packed zeros stay unused
+        // O
+        a = PackArgs{};
+        a.kind = PACK_PLAIN; a.src0 = w.wo; a.dst = p.o.wp; a.N = p.o.N; a.K = p.o.K; a.nkt = p.o.nkt; a.NT = p.o.NT; a.n_groups = p.o.n_groups;
+        launch_pack(desc->dtype, a, s);
+        // gate / up (FFN RMSNorm gain folded in)
+        a = PackArgs{};
+        a.kind = PACK_GATEUP; a.src0 = w.w_gate; a.src1 = w.w_up; a.gain = w.rms_ffn; a.dst = p.gu.wp;
+        a.N = p.gu.N; a.K = p.gu.K; a.nkt = p.gu.nkt; a.NT = p.gu.NT; a.n_groups = p.gu.n_groups;
+        launch_pack(desc->dtype, a, s);
+        // down
+        a = PackArgs{};
+        a.kind = PACK_PLAIN; a.src0 = w.w_down; a.dst = p.down.wp; a.N = p.down.N; a.K = p.down.K; a.nkt = p.down.nkt; a.NT = p.down.NT;
+        a.n_groups = p.down.n_groups;
+        launch_pack(desc->dtype, a, s);
+    }
+    if (desc->vocab > 0) {
+        GemmPlan& g = st->L.head;
+        g.wp = st->ws + (size_t)g.wp;
+        PackArgs a{};
+        a.kind = PACK_PLAIN; a.src0 = lm_head; a.gain = final_norm; a.dst = g.wp; a.N = g.N; a.K = g.K; a.nkt = g.nkt; a.NT = g.NT;
+        a.n_groups = g.n_groups;
+        launch_pack(desc->dtype, a, s);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        delete st;
+        return FS_EHIP;
+    }
+    *out = st;
+    return FS_OK;
+}
+
+int fs_stage_destroy(fs_stage* stage) {
+    delete stage;
+    return FS_OK;
+}
+
+int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const void* hidden_in, int seg_off, int l_s, const int32_t* parent,
+                         void* hidden_out, void* stream) {
+    if (!st || l_s < 0 || seg_off < 0 || l_glo < 0) return FS_EINVAL;
+    if (l_cache != l_glo + seg_off) return FS_EINVAL;
+    if (l_s == 0) return FS_OK;
+    if (!hidden_in || !hidden_out || !parent) return FS_EINVAL;
+    const fs_stage_desc& d = st->d;
+    const int T = seg_off + l_s;
+    if (T > d.max_tree || l_s > d.max_seg) return FS_ECAP;
+    if ((long long)l_cache + l_s > d.kv_capacity) return FS_ECAP;
+    int rc = valid_kv(d, kv);
+    if (rc) return rc;
+    if (parent[0] != -1) return FS_ETOPO;
+    for (int i = 1; i < T; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return FS_ETOPO;
+    IdxList pl;
+    rc = fill_idx(pl, parent, T);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const int hd = d.head_dim, nq = d.n_q_heads * hd, G = d.n_q_heads / d.n_kv_heads;
+    const Layout& L = st->L;
+    void* q = st->at<void>(L.off_q);
+    void* o = st->at<void>(L.off_o);
+    float* h = st->at<float>(L.off_h);
+    void* hb = st->at<void>(L.off_hb);
+    void* act = st->at<void>(L.off_act);
+    uint64_t* anc = st->at<uint64_t>(L.off_anc);
+    float2* rope = st->at<float2>(L.off_rope);
+
+    HIP_TRY(launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, d.rope_theta, anc, rope, s));
+
+    AttnArgs at{};
+    at.q = q; at.o = o; at.M = l_s; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
+    at.l_glo = l_glo; at.L = l_cache + l_s; at.anc = anc;
+    at.scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
+    at.stride_kv = kv.stride_kv; at.stride_head = kv.stride_head; at.stride_tok = kv.stride_tok;
+    at.part_o = st->at<float>(L.off_po); at.part_ml = st->at<float>(L.off_pml);
+    at.Rpad = (int)align_up((size_t)G * l_s, 16);
+    int aNW, aMTW, aRB;
+    attn_plan(st->elem, hd, l_s, G, d.n_kv_heads, at.L, kMaxSplits, &aNW, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
+
+    for (int l = 0; l < d.n_layers; ++l) {
+        const LayerPlan& p = L.layers[l];
+        unsigned char* klayer = (unsigned char*)kv.base + (size_t)l * kv.stride_layer * st->elem;
+        const bool first = (l == 0), last = (l == d.n_layers - 1);
+        // RMSNorm + QKV + RoPE + cache append
+        GemmArgs g{};
+        g.X = first ? hidden_in : hb; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
+        g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
+        g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
+        g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
+        HIP_TRY(launch_gemm(d.dtype, EPI_QKV, p.qkv.NT, p.qkv.NW, p.qkv.n_groups, g, s));
+        // tree attention
+        at.k_layer = klayer;
+        HIP_TRY(launch_attention(d.dtype, at, aNW, aMTW, aRB, s));
+        // output projection + residual
+        g = GemmArgs{};
+        g.X = o; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
+        g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb;
+        HIP_TRY(launch_gemm(d.dtype, EPI_RESID, p.o.NT, p.o.NW, p.o.n_groups, g, s));
+        // RMSNorm + gate/up + SiLU * up
+        g = GemmArgs{};
+        g.X = hb; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
+        g.act_out = act; g.F = d.d_ffn;
+        HIP_TRY(launch_gemm(d.dtype, EPI_SWIGLU, p.gu.NT, p.gu.NW, p.gu.n_groups, g, s));
+        // down projection + residual
+        g = GemmArgs{};
+        g.X = act; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
+        g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb;
+        HIP_TRY(launch_gemm(d.dtype, EPI_RESID, p.down.NT, p.down.NW, p.down.n_groups, g, s));
+    }
+    return FS_OK;
+}
+
+int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int32_t* amax, void* stream) {
+    if (!st || l_s < 0) return FS_EINVAL;
+    if (st->d.vocab <= 0) return FS_EINVAL;
+    if (l_s == 0) return FS_OK;
+    if (!hidden || !logits || !amax) return FS_EINVAL;
+    if (l_s > st->d.max_seg) return FS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const GemmPlan& p = st->L.head;
+    GemmArgs g{};
+    g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
+    HIP_TRY(launch_gemm(st->d.dtype, EPI_LOGITS, p.NT, p.NW, p.n_groups, g, s));
+    HIP_TRY(launch_argmax(logits, l_s, st->d.vocab, FS_ARGMAX_CHUNKS, st->at<int32_t>(st->L.off_amw), amax, s));
+    return FS_OK;
+}
+
+int fs_tree_accept(const float* logits, int32_t* amax, int vocab, const int32_t* token, const int32_t* parent, int T, int n_ver,
+                   fs_accept_result* res, int32_t* retain, int32_t* work, void* stream) {
+    if (!token || !parent || !res || !retain || T < 1 || n_ver < 0 || n_ver > T) return FS_EINVAL;
+    if (T > FS_MAX_TREE) return FS_ECAP;
+    if (n_ver > 0 && !amax) return FS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (logits && n_ver > 0) {
+        if (vocab < 1 || !work) return FS_EINVAL;
+        HIP_TRY(launch_argmax(logits, n_ver, vocab, FS_ARGMAX_CHUNKS, work, amax, s));
+    }
+    static_assert(sizeof(fs_accept_result) == sizeof(AcceptResultDev), "result layouts must agree");
+    HIP_TRY(launch_accept(amax, token, parent, T, n_ver, (AcceptResultDev*)res, retain, s));
+    return FS_OK;
+}
+
+int fs_accept_result_to_host(const fs_accept_result* res_dev, const int32_t* retain_dev, int T, fs_accept_result* res_host, int32_t* retain_host,
+                             void* stream) {
+    if (!res_dev || !res_host || T < 0) return FS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(res_host, res_dev, sizeof(fs_accept_result), hipMemcpyDeviceToHost, s));
+    if (retain_dev && retain_host && T > 0) HIP_TRY(hipMemcpyAsync(retain_host, retain_dev, sizeof(int32_t) * (size_t)T, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return FS_OK;
+}
+
+int fs_kv_compact(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const int32_t* retain, const fs_accept_result* res, int n_retain_host,
+                  int n_acc_host, int32_t* new_len, void* stream) {
+    if (!st || !retain || l_glo < 0 || l_cache < l_glo) return FS_EINVAL;
+    const fs_stage_desc& d = st->d;
+    if (l_cache > d.kv_capacity) return FS_ECAP;
+    int rc = valid_kv(d, kv);
+    if (rc) return rc;
+    CompactArgs a{};
+    IdxList host;
+    host.n = 0;
+    if (res) {
+        a.retain_dev = retain;
+        a.res_dev = (const AcceptResultDev*)res;
+    } else {
+        if (n_retain_host < 0 || n_acc_host < 0 || n_acc_host > n_retain_host) return FS_EINVAL;
+        if (n_retain_host > FS_MAX_TREE) return FS_ECAP;
+        for (int j = 0; j < n_retain_host; ++j)
+            if (retain[j] < 0 || (j > 0 && retain[j] <= retain[j - 1])) return FS_EINVAL;
+        rc = fill_idx(host, retain, n_retain_host);
+        if (rc) return rc;
+        a.n_retain = n_retain_host;
+        a.n_acc = n_acc_host;
+    }
+    a.base = kv.base; a.stride_layer = kv.stride_layer; a.stride_kv = kv.stride_kv; a.stride_head = kv.stride_head; a.stride_tok = kv.stride_tok;
+    a.elem_bytes = st->elem; a.n_layers = d.n_layers; a.n_kv_heads = d.n_kv_heads; a.hd = d.head_dim;
+    a.l_glo = l_glo; a.l_cache = l_cache; a.new_len = new_len;
+    // split rows over column blocks until the grid has a few workgroups per compute unit
+    const int ppr = d.head_dim * st->elem / 16;
+    int cb = 1;
+    while ((long long)d.n_layers * 2 * d.n_kv_heads * cb < 512 && cb * 2 <= ppr) cb *= 2;
+    a.colblocks = cb;
+    HIP_TRY(launch_kv_compact(a, host, (hipStream_t)stream));
+    return FS_OK;
+}
+
+int fs_seg_prune(const void* seg_in, int l_s, size_t row_bytes, int off, const int32_t* retain, const fs_accept_result* res, int n_retain_host,
+                 void* seg_out, int32_t* l_s_out, void* stream) {
+    if (l_s < 0 || off < 0 || !retain || (row_bytes & 3) || row_bytes == 0) return FS_EINVAL;
+    if (l_s > 0 && (!seg_in || !seg_out || seg_in == seg_out)) return FS_EINVAL;
+    IdxList host;
+    host.n = 0;
+    const int32_t* rdev = nullptr;
+    if (res) {
+        rdev = retain;
+    } else {
+        if (n_retain_host < 0) return FS_EINVAL;
+        if (n_retain_host > FS_MAX_TREE) return FS_ECAP;
+        for (int j = 0; j < n_retain_host; ++j)
+            if (retain[j] < 0 || (j > 0 && retain[j] <= retain[j - 1])) return FS_EINVAL;
+        int rc = fill_idx(host, retain, n_retain_host);
+        if (rc) return rc;
+    }
+    HIP_TRY(launch_seg_prune(seg_in, l_s, row_bytes, off, rdev, (const AcceptResultDev*)res, host, seg_out, l_s_out, (hipStream_t)stream));
+    return FS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,322 @@
+// Skinny-M projection kernels and the one-time weight re-tiling.
+//
+// Work decomposition: workgroup (grp, mb) owns NT consecutive 16-feature tiles ("group" grp) for the
+// MT*16 rows of row block mb.  Its NW waves split the K range; wave w streams the weight fragments
+// of k-tiles [nkt*w/NW, nkt*(w+1)/NW) — one contiguous run of NT KiB per k-tile in the re-tiled
+// layout — and multiplies them with the activation fragments of the same k-tiles (read through L2).
+// Partial 16x16 tiles are summed across waves through LDS, then the epilogue runs on the reduced tile.
+//
+// Operand roles: A = weights (rows = output features), B = activations (rows = segment rows), so the
+// result tile is Y^T: lane l holds features n = (l/16)*4 + v, v = 0..3, of row m = l % 16 — four
+// consecutive features of one row per lane: vector stores, and per-row scalars (RMSNorm scale) are
+// per-lane.
+//
+// RMSNorm is split algebraically: norm(x) . w = rs(x) * sum_k x_k g_k w_k.  The gain g is folded into the
+// re-tiled weights once; rs(x) = rsqrt(mean(x^2) + eps) is computed from the activation fragments the
+// workgroup reads anyway (it covers the whole K range) and applied in the epilogue.
+#include "gemm.hpp"
+
+#define PF 4 /* k-steps of loads kept in flight per wave */
+
+template <typename T>
+static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p) {
+    using frag_t = typename Elem<T>::frag_t;
+    return __builtin_nontemporal_load((const frag_t*)p);
+}
+
+template <typename T, int MT, int NT, int EPI>
+__global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
+    using E = Elem<T>;
+    using frag_t = typename E::frag_t;
+    constexpr bool NORM = (EPI != EPI_RESID);
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, NW = blockDim.x >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int grp = blockIdx.x, mb = blockIdx.y;
+    const int row0 = mb * MT * 16;
+
+    const int kt0 = (int)(((long long)a.nkt * w) / NW), kt1 = (int)(((long long)a.nkt * (w + 1)) / NW);
+    const unsigned char* wbase = (const unsigned char*)a.Wp + ((size_t)grp * a.nkt) * (size_t)(NT * 1024) + (size_t)lane * 16;
+    const T* xrow[MT];
+    bool xok[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int m = row0 + mt * 16 + r16;
+        xok[mt] = m < a.M;
+        xrow[mt] = (const T*)a.X + (size_t)(xok[mt] ? m : 0) * a.ldx + g * E::EPF;
+    }
+
+    f32x4 acc[MT][NT];
+    float ss[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        ss[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    frag_t bq[PF][NT], aq[PF][MT];
+    auto issue = [&](int s, int kt) {
+        const unsigned char* wp = wbase + (size_t)kt * (NT * 1024);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bq[s][nt] = load_w<T>(wp + nt * 1024);
+        const int k = kt * E::KT + g * E::EPF;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            // K is a multiple of EPF, so a fragment is either fully inside or fully outside the row
+            aq[s][mt] = (xok[mt] && k < a.K) ? *(const frag_t*)(xrow[mt] + (size_t)kt * E::KT) : E::zero();
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+        if (kt0 + s < kt1) issue(s, kt0 + s);
+    for (int kt = kt0; kt < kt1; kt += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            if (kt + s < kt1) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if (NORM) ss[mt] += E::sumsq(aq[s][mt]);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = E::mma(bq[s][nt], aq[s][mt], acc[mt][nt]);
+                }
+                if (kt + s + PF < kt1) issue(s, kt + s + PF);
+            }
+        }
+    }
+
+    // ---- cross-wave reduction through LDS ---------------------------------------------------------
+    float* red = (float*)smem;                       // [NW][MT*NT][4][64]
+    float* ssr = red + (size_t)NW * MT * NT * 256;   // [NW][MT][16]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(((size_t)w * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane] = acc[mt][nt][v];
+        if (NORM) {
+            float t = wave_xor_add(wave_xor_add(ss[mt], 16), 32);
+            if (lane < 16) ssr[(w * MT + mt) * 16 + lane] = t;
+        }
+    }
+    __syncthreads();
+
+    // ---- epilogue: an "item" is one 16x16 tile (RESID, LOGITS) or a pair of tiles (QKV, SWIGLU) ---
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    constexpr int TPI = PAIR ? 2 : 1;  // tiles per item
+    constexpr int ITEMS = MT * NT / TPI;
+    static_assert(!PAIR || NT % 2 == 0, "paired epilogues need an even NT");
+    for (int item = w; item < ITEMS; item += NW) {
+        const int mt = item / (NT / TPI), ntp = item % (NT / TPI);
+        const int m = row0 + mt * 16 + r16;
+        float y[TPI][4];
+#pragma unroll
+        for (int t = 0; t < TPI; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float s = 0.f;
+                for (int ww = 0; ww < NW; ++ww) s += red[(((size_t)ww * MT * NT + mt * NT + ntp * TPI + t) * 4 + v) * 64 + lane];
+                y[t][v] = s;
+            }
+        float rs = 1.f;
+        if (NORM) {
+            float s = 0.f;
+            for (int ww = 0; ww < NW; ++ww) s += ssr[(ww * MT + mt) * 16 + r16];
+            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+        }
+        if (m >= a.M) continue;
+        const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
+        if (EPI == EPI_RESID) {
+            const int n = ptile * 16 + g * 4;
+            if (n < a.N) {
+                float r[4];
+                if (a.resid_is_T) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
+                } else {
+                    f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) r[v] = rv[v];
+                }
+                f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
+                *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
+                *(typename E::out4_t*)((T*)a.hb_out + (size_t)m * a.N + n) = E::pack4(h[0], h[1], h[2], h[3]);
+            }
+        } else if (EPI == EPI_LOGITS) {
+            const int n = ptile * 16 + g * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
+        } else if (EPI == EPI_SWIGLU) {
+            const int f = (ptile >> 1) * 16 + g * 4;
+            if (f < a.F) {
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float gt = rs * y[0][v], up = rs * y[1][v];
+                    o[v] = gt / (1.0f + expf(-gt)) * up;
+                }
+                *(typename E::out4_t*)((T*)a.act_out + (size_t)m * a.F + f) = E::pack4(o[0], o[1], o[2], o[3]);
+            }
+        } else {  // EPI_QKV
+            const int tph = a.hd >> 4;  // tiles per head
+            const int head = ptile / tph, tih = ptile % tph;
+            float lo[4], hi[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                lo[v] = rs * y[0][v];
+                hi[v] = rs * y[1][v];
+                if (a.bias) {
+                    lo[v] += a.bias[ptile * 16 + g * 4 + v];
+                    hi[v] += a.bias[(ptile + 1) * 16 + g * 4 + v];
+                }
+            }
+            if (head < a.Hq + a.Hkv) {
+                // q / k head: the pair holds features t and t + hd/2, t = (tih/2)*16 + g*4 + v
+                const int t = (tih >> 1) * 16 + g * 4, half = a.hd >> 1;
+                const float2* cs = a.rope + (size_t)m * half + t;
+                float olo[4], ohi[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float2 c = cs[v];
+                    olo[v] = lo[v] * c.x - hi[v] * c.y;
+                    ohi[v] = hi[v] * c.x + lo[v] * c.y;
+                }
+                T* dst;
+                if (head < a.Hq)
+                    dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
+                else
+                    dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+                *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
+                *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
+            } else if (head < a.Hq + 2 * a.Hkv) {
+                // v head: natural tile order, no rotation
+                T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+                const int t = tih * 16 + g * 4;
+                *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
+                *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);
+            }
+        }
+    }
+}
+
+template <typename T, int MT, int NT, int EPI>
+static hipError_t launch_one(int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    const int mblocks = (a.M + MT * 16 - 1) / (MT * 16);
+    const size_t lds = (size_t)NW * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
+    hipLaunchKernelGGL((skinny_gemm_kernel<T, MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int EPI>
+static hipError_t launch_mt_nt(int MT, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+#define FS_CASE(mt, nt) \
+    if (MT == mt && NT == nt) return launch_one<T, mt, nt, EPI>(NW, n_groups, a, s);
+    if constexpr (!PAIR) {
+        FS_CASE(1, 1) FS_CASE(2, 1) FS_CASE(4, 1)
+    }
+    FS_CASE(1, 2) FS_CASE(2, 2) FS_CASE(4, 2) FS_CASE(1, 4) FS_CASE(2, 4) FS_CASE(4, 4)
+#undef FS_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    const int MT = a.M <= 16 ? 1 : (a.M <= 32 ? 2 : 4);
+    // LDS for the cross-wave reduction grows with NW*MT*NT KiB; keep it within 64 KiB
+    while (NW > 1 && (size_t)NW * MT * NT * 1024 > 60 * 1024) NW >>= 1;
+#define FS_EPI(e)                                                                      \
+    if (epi == e) {                                                                    \
+        if (dtype == 0) return launch_mt_nt<float, e>(MT, NT, NW, n_groups, a, s);     \
+        return launch_mt_nt<bf16_t, e>(MT, NT, NW, n_groups, a, s);                    \
+    }
+    FS_EPI(EPI_QKV) FS_EPI(EPI_RESID) FS_EPI(EPI_SWIGLU) FS_EPI(EPI_LOGITS)
+#undef FS_EPI
+    return hipErrorInvalidValue;
+}
+
+// ---- one-time weight re-tiling ------------------------------------------------------------------
+// One thread per 16-byte fragment slot of the destination.  Rows of Q and K heads are re-ordered so that
+// tiles (2i, 2i+1) of a head hold features [16i, 16i+16) and [hd/2 + 16i, hd/2 + 16i + 16): the two halves
+// of the rotary pairs land in one workgroup.  Gate and up rows alternate tile by tile so that silu(gate)*up
+// is formed in the epilogue.  Rows / columns beyond N / K are zero.
+template <typename T>
+__global__ void pack_kernel(const PackArgs a) {
+    using E = Elem<T>;
+    const size_t total = (size_t)a.n_groups * a.nkt * a.NT * 64;
+    for (size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x; c < total; c += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(c & 63);
+        size_t t = c >> 6;
+        const int nt = (int)(t % a.NT);
+        t /= a.NT;
+        const int kt = (int)(t % a.nkt);
+        const int grp = (int)(t / a.nkt);
+        const int r = lane & 15, g = lane >> 4;
+        const int ptile = grp * a.NT + nt;
+        const int k = kt * E::KT + g * E::EPF;
+        const T* src = nullptr;
+        long long row = -1;
+        if (a.kind == PACK_PLAIN) {
+            row = (long long)ptile * 16 + r;
+            src = (const T*)a.src0;
+            if (row >= a.N) row = -1;
+        } else if (a.kind == PACK_GATEUP) {
+            row = (long long)(ptile >> 1) * 16 + r;
+            src = (const T*)((ptile & 1) ? a.src1 : a.src0);
+            if (row >= a.N) row = -1;  // N = d_ffn here
+        } else {
+            const int tph = a.hd >> 4;
+            const int head = ptile / tph, tih = ptile % tph;
+            if (head < a.Hq + a.Hkv) {
+                const int orig = (tih >> 1) + (tih & 1) * (tph >> 1);
+                const int hh = head < a.Hq ? head : head - a.Hq;
+                src = (const T*)(head < a.Hq ? a.src0 : a.src1);
+                row = (long long)hh * a.hd + orig * 16 + r;
+            } else if (head < a.Hq + 2 * a.Hkv) {
+                src = (const T*)a.src2;
+                row = (long long)(head - a.Hq - a.Hkv) * a.hd + tih * 16 + r;
+            }
+        }
+        typename E::frag_t f = E::zero();
+        if (row >= 0 && k < a.K) {
+#pragma unroll
+            for (int e = 0; e < E::EPF; ++e) {
+                float v = E::to_f(src[(size_t)row * a.K + k + e]);
+                if (a.gain) v *= E::to_f(((const T*)a.gain)[k + e]);
+                f[e] = E::from_f(v);
+            }
+        }
+        ((typename E::frag_t*)a.dst)[c] = f;
+    }
+    // packed-order bias (QKV only)
+    if (a.kind == PACK_QKV && a.bias_dst) {
+        const int np = a.n_groups * a.NT * 16;
+        for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < np; i += gridDim.x * blockDim.x) {
+            const int ptile = i >> 4, r = i & 15;
+            const int tph = a.hd >> 4;
+            const int head = ptile / tph, tih = ptile % tph;
+            float v = 0.f;
+            if (head < a.Hq + a.Hkv) {
+                const int orig = (tih >> 1) + (tih & 1) * (tph >> 1);
+                const int hh = head < a.Hq ? head : head - a.Hq;
+                const T* b = (const T*)(head < a.Hq ? a.b0 : a.b1);
+                if (b) v = E::to_f(b[hh * a.hd + orig * 16 + r]);
+            } else if (head < a.Hq + 2 * a.Hkv) {
+                const T* b = (const T*)a.b2;
+                if (b) v = E::to_f(b[(head - a.Hq - a.Hkv) * a.hd + tih * 16 + r]);
+            }
+            a.bias_dst[i] = v;
+        }
+    }
+}
+
+void launch_pack(int dtype, const PackArgs& a, hipStream_t s) {
+    const size_t total = (size_t)a.n_groups * a.nkt * a.NT * 64;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 65536) blocks = 65536;
+    if (blocks < 1) blocks = 1;
+    if (dtype == 0)
+        hipLaunchKernelGGL(pack_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(pack_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, a);
+}

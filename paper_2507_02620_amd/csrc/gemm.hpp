@@ -1,0 +1,58 @@
+// Skinny-M projection kernels: Y[M, N] = X[M, K] * W^T with M = segment length (<= 64 rows per pass).
+// At these row counts every weight byte is used by only M rows, so the kernels are built around one
+// coalesced pass over a re-tiled copy of W (the HBM stream is the roofline, the MFMA work rides along).
+#pragma once
+#include "common.hpp"
+
+enum GemmEpilogue {
+    EPI_QKV = 0,    // RMSNorm scale, bias, rotary embedding, write q and the K/V cache rows   (layer step: norm + QKV + RoPE + append)
+    EPI_RESID = 1,  // residual add, write the fp32 residual stream and its T-typed copy       (output / down projection)
+    EPI_SWIGLU = 2, // RMSNorm scale, silu(gate) * up                                           (gate / up projection)
+    EPI_LOGITS = 3  // RMSNorm scale, fp32 logits                                               (LM head)
+};
+
+enum PackKind { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
+
+struct GemmArgs {
+    const void* X;   // [M][ldx] activations, element type T
+    const void* Wp;  // re-tiled weights: [n_groups][nkt][NT][64 lanes][16 bytes]
+    int ldx, M, K, nkt;
+    int N;           // valid output features (packed order)
+    float eps;
+    const float* bias;  // packed order, or null
+    // EPI_QKV
+    const float2* rope;  // [M][hd/2] (cos, sin)
+    void* q_out;         // [M][Hq*hd]
+    void* k_layer;       // K cache of this layer (kv = 0), V at + stride_kv
+    long long stride_kv, stride_head, stride_tok;
+    int Hq, Hkv, hd, slot0;
+    // EPI_RESID
+    const void* resid;  // [M][N] fp32 residual stream, or T-typed stage input when resid_is_T
+    int resid_is_T;
+    float* h_out;  // [M][N] fp32
+    void* hb_out;  // [M][N] T
+    // EPI_SWIGLU
+    void* act_out;  // [M][F]
+    int F;
+    // EPI_LOGITS
+    float* logits;  // [M][vocab]
+};
+
+struct PackArgs {
+    const void* src0;  // PLAIN: W; QKV: wq; GATEUP: w_gate
+    const void* src1;  // QKV: wk; GATEUP: w_up
+    const void* src2;  // QKV: wv
+    const void* gain;  // [K] RMSNorm gain folded into the columns, or null
+    void* dst;
+    int kind, N, K, nkt, NT, n_groups;
+    int Hq, Hkv, hd;
+    // bias (QKV only): packed fp32 copy
+    const void* b0;
+    const void* b1;
+    const void* b2;
+    float* bias_dst;
+};
+
+void launch_pack(int dtype, const PackArgs& a, hipStream_t s);
+// MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
+hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);

@@ -1,0 +1,27 @@
+// Tree bookkeeping, acceptance, KV-cache and segment pruning: launch interface (see tree.hip).
+#pragma once
+#include "common.hpp"
+
+struct AcceptResultDev {
+    int32_t n_acc, x_new, n_new, continuous, n_retain, n_pr_verified;
+};
+
+struct CompactArgs {
+    void* base;
+    long long stride_layer, stride_kv, stride_head, stride_tok;  // elements
+    int elem_bytes, n_layers, n_kv_heads, hd;
+    int l_glo, l_cache, colblocks;
+    const int32_t* retain_dev;         // device list, or null -> use `host` below
+    const AcceptResultDev* res_dev;    // counts on the device (with retain_dev)
+    int n_retain, n_acc;               // counts for the host list
+    int32_t* new_len;                  // optional [2]
+};
+
+hipError_t launch_tree_prepare(const IdxList& parent, int l_glo, int seg_off, int l_s, int hd, float theta, uint64_t* anc, float2* rope,
+                               hipStream_t s);
+hipError_t launch_argmax(const float* logits, int rows, int vocab, int chunks, int32_t* work, int32_t* amax, hipStream_t s);
+hipError_t launch_accept(const int32_t* amax, const int32_t* token, const int32_t* parent, int T, int n_ver, AcceptResultDev* res,
+                         int32_t* retain, hipStream_t s);
+hipError_t launch_kv_compact(const CompactArgs& a, const IdxList& host, hipStream_t s);
+hipError_t launch_seg_prune(const void* seg_in, int l_s, size_t row_bytes, int off, const int32_t* retain_dev, const AcceptResultDev* res_dev,
+                            const IdxList& host, void* seg_out, int32_t* l_s_out, hipStream_t s);

@@ -1,0 +1,236 @@
+"""Thin ctypes binding over libflowspec_hip.so (include/flowspec.h): argument marshalling only.
+
+PyTorch supplies device memory (`tensor.data_ptr()`) and the stream; every step of the path runs in
+the library's HIP kernels.  If the library has not been built (`python -m paper_2507_02620_amd.build`)
+importing this module raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflowspec_hip.so")
+
+FS_OK, FS_EINVAL, FS_ETOPO, FS_ECAP, FS_EDTYPE, FS_EHIP, FS_EWS = 0, -1, -2, -3, -4, -5, -6
+FS_F32, FS_BF16 = 0, 1
+FS_MAX_TREE = 1024
+FS_ARGMAX_CHUNKS = 64
+_ERR = {FS_EINVAL: "FS_EINVAL", FS_ETOPO: "FS_ETOPO", FS_ECAP: "FS_ECAP", FS_EDTYPE: "FS_EDTYPE", FS_EHIP: "FS_EHIP", FS_EWS: "FS_EWS"}
+
+EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_tree_verify_stage",
+           "fs_tree_logits", "fs_tree_accept", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune")
+
+
+class FlowSpecError(RuntimeError):
+    def __init__(self, code, what, hip=0):
+        super().__init__(f"{what}: {_ERR.get(code, code)}" + (f" (hipError {hip})" if code == FS_EHIP else ""))
+        self.code = code
+        self.hip = hip
+
+
+class StageDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("d_model", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("d_ffn", C.c_int), ("vocab", C.c_int), ("dtype", C.c_int), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("kv_capacity", C.c_int), ("max_tree", C.c_int), ("max_seg", C.c_int)]
+
+
+_W = ("rms_attn", "wq", "wk", "wv", "wo", "rms_ffn", "w_gate", "w_up", "w_down", "bq", "bk", "bv")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W]
+
+
+class KVCache(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("stride_layer", C.c_longlong), ("stride_kv", C.c_longlong), ("stride_head", C.c_longlong),
+                ("stride_tok", C.c_longlong)]
+
+
+class AcceptResult(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_acc", "x_new", "n_new", "continuous", "n_retain", "n_pr_verified")]
+
+    def as_tuple(self):
+        return tuple(int(getattr(self, n)) for n, _ in self._fields_)
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_02620_amd.build` (no fallback path exists)")
+    lib = C.CDLL(LIB_PATH)
+    vp, ci, i32p = C.c_void_p, C.c_int, C.c_void_p
+    lib.fs_stage_workspace_bytes.restype = C.c_size_t
+    lib.fs_stage_workspace_bytes.argtypes = [C.POINTER(StageDesc)]
+    lib.fs_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), vp, vp, vp, C.c_size_t, vp, C.POINTER(vp)]
+    lib.fs_stage_destroy.argtypes = [vp]
+    lib.fs_tree_verify_stage.argtypes = [vp, KVCache, ci, ci, vp, ci, ci, i32p, vp, vp]
+    lib.fs_tree_logits.argtypes = [vp, vp, ci, vp, vp, vp]
+    lib.fs_tree_accept.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, vp]
+    lib.fs_accept_result_to_host.argtypes = [vp, vp, ci, C.POINTER(AcceptResult), i32p, vp]
+    lib.fs_kv_compact.argtypes = [vp, KVCache, ci, ci, vp, vp, ci, ci, vp, vp]
+    lib.fs_seg_prune.argtypes = [vp, ci, C.c_size_t, ci, vp, vp, ci, vp, vp, vp]
+    for n in EXPORTS:
+        if n not in ("fs_stage_workspace_bytes",):
+            getattr(lib, n).restype = C.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def lib():
+    return _lib
+
+
+def _check(rc, what):
+    if rc != FS_OK:
+        raise FlowSpecError(rc, what, _lib.fs_last_hip_error() if rc == FS_EHIP else 0)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dp(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _host_i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def torch_dtype(code):
+    return torch.float32 if code == FS_F32 else torch.bfloat16
+
+
+def kv_descriptor(kv: torch.Tensor) -> KVCache:
+    """kv: device tensor [n_layers, 2, n_kv_heads, capacity, head_dim] (any strides with a contiguous last dim)."""
+    assert kv.dim() == 5 and kv.shape[1] == 2 and kv.stride(4) == 1
+    return KVCache(kv.data_ptr(), kv.stride(0), kv.stride(1), kv.stride(2), kv.stride(3))
+
+
+class Stage:
+    """One verification stage: owns the workspace tensor and the opaque handle."""
+
+    def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype, rms_eps, rope_theta, kv_capacity,
+                 max_tree, max_seg, layers, final_norm=None, lm_head=None, device="cuda", stream=None):
+        self.desc = StageDesc(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype, rms_eps, rope_theta, kv_capacity,
+                              max_tree, max_seg)
+        self.dtype = torch_dtype(dtype)
+        self.device = torch.device(device)
+        nbytes = _lib.fs_stage_workspace_bytes(C.byref(self.desc))
+        if nbytes == 0:
+            # let the library name the reason
+            h = C.c_void_p()
+            _check(_lib.fs_stage_create(C.byref(self.desc), None, None, None, None, 0, None, C.byref(h)) or FS_EINVAL, "fs_stage_create")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        arr = (LayerWeights * n_layers)()
+        for i, lw in enumerate(layers):
+            for n in _W:
+                t = lw.get(n)
+                if t is not None:
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == self.dtype, n
+                setattr(arr[i], n, None if t is None else t.data_ptr())
+        self._handle = C.c_void_p()
+        _check(_lib.fs_stage_create(C.byref(self.desc), arr, _dp(final_norm), _dp(lm_head), C.c_void_p(self._ws_ptr), nbytes, _stream(stream),
+                                    C.byref(self._handle)), "fs_stage_create")
+        self.workspace_bytes = nbytes
+
+    def close(self):
+        if getattr(self, "_handle", None):
+            _lib.fs_stage_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        self.close()
+
+    def new_kv_cache(self) -> torch.Tensor:
+        d = self.desc
+        return torch.zeros((d.n_layers, 2, d.n_kv_heads, d.kv_capacity, d.head_dim), dtype=self.dtype, device=self.device)
+
+    def tree_verify_stage(self, kv, l_glo, l_cache, hidden_in, seg_off, parent, hidden_out=None, stream=None):
+        l_s = int(hidden_in.shape[0])
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        par, pp = _host_i32(parent)
+        assert par.shape[0] >= seg_off + l_s
+        _check(_lib.fs_tree_verify_stage(self._handle, kv_descriptor(kv), int(l_glo), int(l_cache), _dp(hidden_in), int(seg_off), l_s, pp,
+                                         _dp(hidden_out), _stream(stream)), "fs_tree_verify_stage")
+        return hidden_out
+
+    def tree_logits(self, hidden, logits=None, amax=None, stream=None):
+        l_s = int(hidden.shape[0])
+        if logits is None:
+            logits = torch.empty((l_s, self.desc.vocab), dtype=torch.float32, device=self.device)
+        if amax is None:
+            amax = torch.empty((l_s,), dtype=torch.int32, device=self.device)
+        _check(_lib.fs_tree_logits(self._handle, _dp(hidden), l_s, _dp(logits), _dp(amax), _stream(stream)), "fs_tree_logits")
+        return logits, amax
+
+    def kv_compact(self, kv, l_glo, l_cache, retain, res=None, n_acc=None, new_len=None, stream=None):
+        """retain: device int32 tensor together with `res` (device AcceptResult buffer), or a host sequence with n_acc."""
+        if res is not None:
+            _check(_lib.fs_kv_compact(self._handle, kv_descriptor(kv), int(l_glo), int(l_cache), _dp(retain), _dp(res), 0, 0, _dp(new_len),
+                                      _stream(stream)), "fs_kv_compact")
+        else:
+            r, rp = _host_i32(retain)
+            _check(_lib.fs_kv_compact(self._handle, kv_descriptor(kv), int(l_glo), int(l_cache), rp, None, int(r.shape[0]), int(n_acc),
+                                      _dp(new_len), _stream(stream)), "fs_kv_compact")
+
+
+def new_accept_buffers(T, n_ver_max, device="cuda"):
+    """Device buffers for tree_accept: (res [6] int32, retain [T] int32, work int32)."""
+    res = torch.zeros(6, dtype=torch.int32, device=device)
+    retain = torch.zeros(max(T, 1), dtype=torch.int32, device=device)
+    work = torch.zeros(2 * max(n_ver_max, 1) * FS_ARGMAX_CHUNKS, dtype=torch.int32, device=device)
+    return res, retain, work
+
+
+def tree_accept(logits, amax, token, parent, n_ver, res, retain, work=None, stream=None):
+    T = int(token.shape[0])
+    vocab = int(logits.shape[1]) if logits is not None else 0
+    _check(_lib.fs_tree_accept(_dp(logits), _dp(amax), vocab, _dp(token), _dp(parent), T, int(n_ver), _dp(res), _dp(retain), _dp(work),
+                               _stream(stream)), "fs_tree_accept")
+
+
+def accept_result_to_host(res, retain, T, stream=None):
+    out = AcceptResult()
+    buf = np.zeros(max(T, 1), dtype=np.int32)
+    _check(_lib.fs_accept_result_to_host(_dp(res), _dp(retain), int(T), C.byref(out), buf.ctypes.data_as(C.c_void_p), _stream(stream)),
+           "fs_accept_result_to_host")
+    n = max(out.n_retain, 0)
+    return out, buf[:n].copy()
+
+
+def seg_prune(seg_in, off, retain, res=None, seg_out=None, l_s_out=None, stream=None):
+    l_s = int(seg_in.shape[0])
+    row_bytes = seg_in.element_size() * int(np.prod(seg_in.shape[1:]))
+    if seg_out is None:
+        seg_out = torch.empty_like(seg_in)
+    if l_s_out is None:
+        l_s_out = torch.zeros(1, dtype=torch.int32, device=seg_in.device)
+    if res is not None:
+        _check(_lib.fs_seg_prune(_dp(seg_in), l_s, row_bytes, int(off), _dp(retain), _dp(res), 0, _dp(seg_out), _dp(l_s_out), _stream(stream)),
+               "fs_seg_prune")
+    else:
+        r, rp = _host_i32(retain)
+        _check(_lib.fs_seg_prune(_dp(seg_in), l_s, row_bytes, int(off), rp, None, int(r.shape[0]), _dp(seg_out), _dp(l_s_out), _stream(stream)),
+               "fs_seg_prune")
+    return seg_out, l_s_out
+
+
+def stage_from_config(cfg, layers, final_norm=None, lm_head=None, kv_capacity=None, max_tree=None, max_seg=None, device="cuda"):
+    """Build a Stage from a synth.StageConfig-like object and device weight tensors."""
+    return Stage(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                 d_ffn=cfg.d_ffn, vocab=(cfg.vocab if lm_head is not None else 0), dtype=FS_F32 if cfg.dtype == "f32" else FS_BF16,
+                 rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, kv_capacity=kv_capacity or cfg.kv_capacity,
+                 max_tree=max_tree or cfg.tree_size, max_seg=max_seg or cfg.seg_len, layers=layers, final_norm=final_norm, lm_head=lm_head,
+                 device=device)

@@ -1,0 +1,66 @@
+"""HIP path vs oracle, element by element, on the same seeded inputs (through the C ABI).  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_02620_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(*a, **k):
+    from tests.gpu_util import Pair
+    return Pair(*a, **k)
+
+
+def _check_stage(cfg, seed, seg_len, head=False, tol=None):
+    from tests.gpu_util import TOL, max_rel_err
+    tol = tol or TOL[cfg.dtype]
+    print(f"[case] {cfg.name} seed={seed} seg_len={seg_len} T={cfg.tree_size} l_glo={cfg.l_glo}", flush=True)
+    p = _pair(cfg, seed, head=head)
+    tree = synth.config_tree(cfg, seed)
+    hid = synth.hidden(cfg, tree.size, 0, seed)
+    o_out, g_out = p.verify_tree(tree.parent, hid, seg_len)
+    err = max_rel_err(g_out, o_out)
+    print(f"  hidden max-rel-err {err:.3e} (tol {tol})", flush=True)
+    assert np.isfinite(g_out).all()
+    assert err < tol
+    # the K/V rows the stage appended for the draft tokens
+    L = cfg.l_glo + tree.size
+    kv_g = p.kv[:, :, :, cfg.l_glo:L].float().cpu().numpy()
+    kv_o = p.orc.kv[:, :, :, cfg.l_glo:L]
+    kerr = max_rel_err(kv_g, kv_o)
+    print(f"  appended K/V max-rel-err {kerr:.3e}", flush=True)
+    assert kerr < tol
+    # prefix untouched, bit for bit
+    for l in range(cfg.n_layers):
+        pre = synth.prefix_kv(cfg, l, p.orc.cap, seed)[:, :, : cfg.l_glo]
+        assert np.array_equal(p.kv[l, :, :, : cfg.l_glo].float().cpu().numpy(), pre)
+    return p, tree, o_out, g_out
+
+
+def test_c1_tiny_fp32_stage():
+    cfg = synth.CONFIGS["C1"]
+    _check_stage(cfg, 0, cfg.seg_len)
+
+
+@pytest.mark.parametrize("seg_len", [5, 16])
+def test_c1_ragged_segments(seg_len):
+    cfg = synth.CONFIGS["C1"].with_(tree_size=37, l_glo=131)
+    _check_stage(cfg, 1, seg_len)
+
+
+SMALL_BF16 = synth.StageConfig("small-bf16", "bf16", 2, 512, 4, 4, 128, 1376, 2000, 200, 40, 16, 6, 4)
+
+
+@pytest.mark.parametrize("name,cfg,seg", [
+    ("mha-128", SMALL_BF16, 16),
+    ("mha-128-ragged24", SMALL_BF16.with_(tree_size=50, l_glo=333), 24),
+    ("gqa-bias", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, qkv_bias=True, rms_eps=1e-6, rope_theta=1e6, l_glo=500,
+                                  tree_size=70), 32),
+    ("hd64", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=8, head_dim=64), 16),
+    ("seg64", SMALL_BF16.with_(tree_size=130, l_glo=1000, max_depth=12), 64),
+    ("f32-hd128", SMALL_BF16.with_(dtype="f32", l_glo=100), 16),
+])
+def test_small_stages(name, cfg, seg):
+    _check_stage(cfg.with_(name=name, seg_len=seg), 2, seg)
