@@ -195,7 +195,7 @@ def random_tree(size: int, max_depth: int, max_branch: int = 0, vocab: int = 320
     Growth: node i draws its parent uniformly among earlier nodes whose depth and child count
     allow it (forest=True also allows -1 for i > 0, the literal tiny-config recipe).  Each
     node gets a confidence U(0,1) (the root 1.0); the cumulative score is the product along
-    the path; a stable descending sort gives S.  Sibling tokens are distinct.
+    the path; a stable descending sort gives S.  Sibling tokens are distinct while the vocabulary allows.
     """
     g = _gen(seed, TID_TREE, stream)
     par = np.full(size, -1, dtype=np.int64)
@@ -227,7 +227,7 @@ def random_tree(size: int, max_depth: int, max_branch: int = 0, vocab: int = 320
         s = used.setdefault(int(new_par[i]), set())
         while True:
             t = int(g.integers(0, vocab))
-            if t not in s:
+            if t not in s or len(s) >= vocab:  # more siblings than token ids: duplicates are unavoidable
                 break
         s.add(t)
         tok[i] = t
