@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification stage hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one synthetic batch, for a LLaMA2-7B-shaped 8-layer last
+stage (workload C2): the 64-node draft tree is verified in 4 score-ordered segments of 16 tokens (stage
+forward + LM head + row argmax each), acceptance is planted on the logits, then greedy accept with the
+continuous condition, KV-cache compaction and pruning of one in-flight segment.  All inputs are resident
+in HBM before the timed region.  One JSON line is printed: verified draft tokens/s of the stage, the
+roofline of the dominant kernel (gate/up projection: HBM weight stream) measured with HIP events, and the
+CPU oracle timed on the host cores for one segment of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary ('traffic_bytes: N'), or None."""
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only; invalidates the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-head", action="store_true", help="time the stage forward alone (an intermediate stage)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_02620_amd import flowspec as fs
+    from paper_2507_02620_amd import synth
+
+    cfg = synth.CONFIGS[args.workload]
+    if args.layers:
+        cfg = cfg.with_(n_layers=args.layers)
+    seed = 0
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    use_head = cfg.vocab > 0 and not args.no_head
+
+    t_setup = time.time()
+    host_layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
+    fn, lm = synth.head_weights(cfg, seed) if use_head else (None, None)
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev, tdt)
+    dev_layers = [{k: up(v) for k, v in lw.items()} for lw in host_layers]
+    dfn, dlm = up(fn), up(lm)
+    stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm)
+    torch.cuda.synchronize()
+    del dev_layers, dfn, dlm
+    torch.cuda.empty_cache()
+    kv = stage.new_kv_cache()
+    for l in range(cfg.n_layers):
+        kv[l].copy_(up(synth.prefix_kv(cfg, l, None, seed)))
+    tree = synth.config_tree(cfg, seed)
+    T = tree.size
+    segs = synth.segments(T, cfg.seg_len)
+    hid = up(synth.hidden(cfg, T, 0, seed))
+    hid_segs = [hid[o:o + n].contiguous() for o, n in segs]
+    out_segs = [torch.empty_like(h) for h in hid_segs]
+    token_d = torch.from_numpy(tree.token).to(dev)
+    parent_d = torch.from_numpy(tree.parent).to(dev)
+    logits = torch.zeros((T, max(cfg.vocab, 1)), dtype=torch.float32, device=dev) if use_head else None
+    amax = torch.zeros(T, dtype=torch.int32, device=dev)
+    res, retain, work = fs.new_accept_buffers(T, T, dev)
+    new_len = torch.zeros(2, dtype=torch.int32, device=dev)
+    pr_out = torch.empty_like(hid_segs[-1])
+    pr_n = torch.zeros(1, dtype=torch.int32, device=dev)
+    plants = synth.resolve_plants(synth.plant_path(tree, T, seed, 0, p_stop=0.0, mean_extra=2.0), tree, max(cfg.vocab, 2))
+    plant_rows = torch.tensor([r for r, _ in plants], dtype=torch.long, device=dev)
+    plant_toks = torch.tensor([t for _, t in plants], dtype=torch.long, device=dev)
+    setup_s = time.time() - t_setup
+
+    def step():
+        l_glo = cfg.l_glo
+        for i, (off, n) in enumerate(segs):
+            stage.tree_verify_stage(kv, l_glo, l_glo + off, hid_segs[i], off, tree.parent[: off + n], out_segs[i])
+            if use_head:
+                stage.tree_logits(out_segs[i], logits[off:off + n], amax[off:off + n])
+        if use_head:
+            logits[plant_rows, plant_toks] += 100.0  # planted acceptance (stand-in for a trained draft model's hit rate)
+            fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work)
+        else:
+            amax[plant_rows] = plant_toks.to(torch.int32)
+            fs.tree_accept(None, amax, token_d, parent_d, T, res, retain, work)
+        stage.kv_compact(kv, l_glo, l_glo + T, retain, res=res, new_len=new_len)
+        fs.seg_prune(hid_segs[-1], segs[-1][0], retain, res=res, seg_out=pr_out, l_s_out=pr_n)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tok_s = T * args.steps / dt
+
+    # second pass of the same steps with the per-kernel event timers armed
+    stage.profile_begin(args.steps * (len(segs) * (2 + 6 * cfg.n_layers) + 4) + 16)
+    for _ in range(args.steps):
+        step()
+    prof = stage.profile_end()
+    out_res, out_ret = fs.accept_result_to_host(res, retain, T)
+
+    elem = 4 if cfg.dtype == "f32" else 2
+    gu_bytes = 2 * cfg.d_ffn * cfg.d_model * elem          # gate + up weights, streamed once per launch
+    gu_ms, gu_n = prof["gateup"]
+    gu_avg_ms = gu_ms / max(gu_n, 1)
+    achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9 if gu_n else 0.0
+    kern = {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1]} for k, v in prof.items() if v[1]}
+    stage_weight_bytes = cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model + 2 * cfg.n_kv_heads * cfg.head_dim * cfg.d_model
+                                         + 3 * cfg.d_ffn * cfg.d_model) * elem
+    head_bytes = cfg.vocab * cfg.d_model * elem if use_head else 0
+    kv_bytes = cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * elem * sum(cfg.l_glo + o + n for o, n in segs)
+    step_bytes = len(segs) * (stage_weight_bytes + head_bytes) + kv_bytes
+
+    result = {
+        "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
+        "value": round(tok_s, 1),
+        "unit": "verified draft tokens/s per stage",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
+                   "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv x {cfg.head_dim}", "d_ffn": cfg.d_ffn, "vocab": cfg.vocab if use_head else 0,
+                   "kv_prefix": cfg.l_glo, "tree_nodes": T, "segment": cfg.seg_len, "segments_per_step": len(segs),
+                   "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs)},
+        "roofline": {"kernel": "skinny_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower()))},
+        "whole_step": {"algorithmic_bytes": step_bytes, "achieved_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                       "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "kernels": kern,
+        "accept": {"n_acc": out_res.n_acc, "continuous": out_res.continuous, "n_retain": out_res.n_retain},
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle  # cpu_baseline leg: the oracle as it stands, timed on the host cores
+        bits = lambda a: None if a is None else synth.f32_to_bf16_bits(a)
+        wl = host_layers if cfg.dtype == "f32" else [{k: bits(v) for k, v in lw.items()} for lw in host_layers]
+        ost = oracle.Stage(cfg, wl, fn if cfg.dtype == "f32" else bits(fn), lm if cfg.dtype == "f32" else bits(lm), None,
+                           bf16_bits=cfg.dtype != "f32")
+        for l in range(cfg.n_layers):
+            ost.load_prefix(l, synth.prefix_kv(cfg, l, None, seed))
+        off, n = segs[0]
+        hs = synth.hidden(cfg, T, 0, seed)[off:off + n]
+        t0 = time.perf_counter()
+        y = ost.verify(cfg.l_glo, cfg.l_glo, hs, 0, tree.parent[:n])
+        if use_head:
+            lg, am = ost.logits(y)
+            oracle.accept(am, tree.token, tree.parent, n)
+        cdt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(n / cdt, 3), "unit": "verified draft tokens/s per stage", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "sample": "1 segment of %d tokens through all %d layers%s, fp64, %.1f s" %
+                                  (n, cfg.n_layers, " + LM head + accept" if use_head else "", cdt)}
+        # the GPU's first segment against the oracle's, as a sanity line (the parity tests are the gate)
+        g = out_segs[0].float().cpu().numpy()
+        result["cpu_baseline"]["gpu_vs_oracle_max_rel_err"] = float(np.abs(g - y).max() / np.abs(y).max())
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

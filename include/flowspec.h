@@ -92,6 +92,29 @@ int fs_stage_create(const fs_stage_desc *desc, const fs_layer_weights *layers, c
                     void *workspace, size_t workspace_bytes, void *stream, fs_stage **out);
 int fs_stage_destroy(fs_stage *stage);
 
+/*
+ * Measurement aid (not part of the method): per-kernel GPU time of the stage's launches.  After
+ * fs_stage_profile_begin every kernel the stage enqueues (verify, logits, compact) is bracketed by a pair of
+ * HIP events on the caller's stream, up to max_records launches (later ones run untimed).
+ * fs_stage_profile_end waits for `stream`, adds up the elapsed milliseconds and launch counts per kernel kind
+ * into total_ms[FS_K_COUNT] / counts[FS_K_COUNT] (host arrays) and disarms the profiler.
+ * The event records perturb back-to-back timing slightly; throughput is measured with the profiler off.
+ */
+enum {
+    FS_K_PREPARE = 0, /* tree mask, positions, rotary table */
+    FS_K_QKV = 1,     /* RMSNorm + Q/K/V projection + RoPE + cache append */
+    FS_K_ATTN = 2,    /* tree attention (+ split merge) */
+    FS_K_OPROJ = 3,   /* output projection + residual */
+    FS_K_GATEUP = 4,  /* RMSNorm + gate/up projection + SiLU*up */
+    FS_K_DOWN = 5,    /* down projection + residual */
+    FS_K_HEAD = 6,    /* final RMSNorm + LM head */
+    FS_K_ARGMAX = 7,  /* row argmax of the logits */
+    FS_K_COMPACT = 8, /* KV-cache compaction */
+    FS_K_COUNT = 9
+};
+int fs_stage_profile_begin(fs_stage *stage, int max_records);
+int fs_stage_profile_end(fs_stage *stage, void *stream, double *total_ms, long long *counts);
+
 /* hipError_t (as int) behind the most recent FS_EHIP on the calling thread, 0 if none. */
 int fs_last_hip_error(void);
 

@@ -21,6 +21,18 @@ static thread_local int g_last_hip = 0;
         }                             \
     } while (0)
 
+// a launch that is timed when the stage's profiler is armed
+#define HIP_TRY_K(st, kind, s, expr)               \
+    do {                                           \
+        const bool t__ = (st)->prof.begin(kind, s); \
+        hipError_t e__ = (expr);                   \
+        if (t__) (st)->prof.end(s);                \
+        if (e__ != hipSuccess) {                   \
+            g_last_hip = (int)e__;                 \
+            return FS_EHIP;                        \
+        }                                          \
+    } while (0)
+
 namespace {
 
 struct GemmPlan {
@@ -157,11 +169,34 @@ int fill_idx(IdxList& L, const int32_t* v, int n) {
 
 }  // namespace
 
+// Optional per-kernel timing: when armed, every launch of the stage is bracketed by a pair of events on the
+// caller's stream; fs_stage_profile_end waits for the stream and sums the elapsed times per kernel kind.
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;  // 2 per record
+    std::vector<int> kind;
+    size_t cap = 0;
+    bool begin(int k, hipStream_t s) {
+        if (!on || kind.size() >= cap) return false;
+        kind.push_back(k);
+        return hipEventRecord(ev[2 * (kind.size() - 1)], s) == hipSuccess;
+    }
+    void end(hipStream_t s) { (void)hipEventRecord(ev[2 * (kind.size() - 1) + 1], s); }
+    void release() {
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        ev.clear();
+        kind.clear();
+        cap = 0;
+        on = false;
+    }
+};
+
 struct fs_stage {
     fs_stage_desc d;
     Layout L;
     unsigned char* ws;
     int elem;
+    Profiler prof;
     template <typename P>
     P* at(size_t off) const { return (P*)(ws + off); }
 };
@@ -249,7 +284,49 @@ int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, c
 }
 
 int fs_stage_destroy(fs_stage* stage) {
+    if (stage) stage->prof.release();
     delete stage;
+    return FS_OK;
+}
+
+int fs_stage_profile_begin(fs_stage* st, int max_records) {
+    if (!st || max_records < 1 || max_records > (1 << 20)) return FS_EINVAL;
+    st->prof.release();
+    st->prof.ev.resize(2 * (size_t)max_records);
+    for (size_t i = 0; i < st->prof.ev.size(); ++i) {
+        hipError_t e = hipEventCreate(&st->prof.ev[i]);
+        if (e != hipSuccess) {
+            st->prof.ev.resize(i);
+            st->prof.release();
+            g_last_hip = (int)e;
+            return FS_EHIP;
+        }
+    }
+    st->prof.cap = (size_t)max_records;
+    st->prof.kind.reserve(st->prof.cap);
+    st->prof.on = true;
+    return FS_OK;
+}
+
+int fs_stage_profile_end(fs_stage* st, void* stream, double* total_ms, long long* counts) {
+    if (!st || !total_ms || !counts) return FS_EINVAL;
+    for (int k = 0; k < FS_K_COUNT; ++k) {
+        total_ms[k] = 0.0;
+        counts[k] = 0;
+    }
+    if (!st->prof.on) return FS_EINVAL;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    for (size_t i = 0; i < st->prof.kind.size() && e == hipSuccess; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, st->prof.ev[2 * i], st->prof.ev[2 * i + 1]);
+        total_ms[st->prof.kind[i]] += ms;
+        counts[st->prof.kind[i]] += 1;
+    }
+    st->prof.release();
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        return FS_EHIP;
+    }
     return FS_OK;
 }
 
@@ -282,7 +359,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     uint64_t* anc = st->at<uint64_t>(L.off_anc);
     float2* rope = st->at<float2>(L.off_rope);
 
-    HIP_TRY(launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, d.rope_theta, anc, rope, s));
+    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, d.rope_theta, anc, rope, s));
 
     AttnArgs at{};
     at.q = q; at.o = o; at.M = l_s; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
@@ -304,25 +381,25 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
         g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
         g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
-        HIP_TRY(launch_gemm(d.dtype, EPI_QKV, p.qkv.NT, p.qkv.NW, p.qkv.n_groups, g, s));
+        HIP_TRY_K(st, FS_K_QKV, s, launch_gemm(d.dtype, EPI_QKV, p.qkv.NT, p.qkv.NW, p.qkv.n_groups, g, s));
         // tree attention
         at.k_layer = klayer;
-        HIP_TRY(launch_attention(d.dtype, at, aNW, aMTW, aRB, s));
+        HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aNW, aMTW, aRB, s));
         // output projection + residual
         g = GemmArgs{};
         g.X = o; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
         g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb;
-        HIP_TRY(launch_gemm(d.dtype, EPI_RESID, p.o.NT, p.o.NW, p.o.n_groups, g, s));
+        HIP_TRY_K(st, FS_K_OPROJ, s, launch_gemm(d.dtype, EPI_RESID, p.o.NT, p.o.NW, p.o.n_groups, g, s));
         // RMSNorm + gate/up + SiLU * up
         g = GemmArgs{};
         g.X = hb; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
-        HIP_TRY(launch_gemm(d.dtype, EPI_SWIGLU, p.gu.NT, p.gu.NW, p.gu.n_groups, g, s));
+        HIP_TRY_K(st, FS_K_GATEUP, s, launch_gemm(d.dtype, EPI_SWIGLU, p.gu.NT, p.gu.NW, p.gu.n_groups, g, s));
         // down projection + residual
         g = GemmArgs{};
         g.X = act; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
         g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb;
-        HIP_TRY(launch_gemm(d.dtype, EPI_RESID, p.down.NT, p.down.NW, p.down.n_groups, g, s));
+        HIP_TRY_K(st, FS_K_DOWN, s, launch_gemm(d.dtype, EPI_RESID, p.down.NT, p.down.NW, p.down.n_groups, g, s));
     }
     return FS_OK;
 }
@@ -337,8 +414,8 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     const GemmPlan& p = st->L.head;
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
-    HIP_TRY(launch_gemm(st->d.dtype, EPI_LOGITS, p.NT, p.NW, p.n_groups, g, s));
-    HIP_TRY(launch_argmax(logits, l_s, st->d.vocab, FS_ARGMAX_CHUNKS, st->at<int32_t>(st->L.off_amw), amax, s));
+    HIP_TRY_K(st, FS_K_HEAD, s, launch_gemm(st->d.dtype, EPI_LOGITS, p.NT, p.NW, p.n_groups, g, s));
+    HIP_TRY_K(st, FS_K_ARGMAX, s, launch_argmax(logits, l_s, st->d.vocab, FS_ARGMAX_CHUNKS, st->at<int32_t>(st->L.off_amw), amax, s));
     return FS_OK;
 }
 
@@ -398,7 +475,7 @@ int fs_kv_compact(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const in
     int cb = 1;
     while ((long long)d.n_layers * 2 * d.n_kv_heads * cb < 512 && cb * 2 <= ppr) cb *= 2;
     a.colblocks = cb;
-    HIP_TRY(launch_kv_compact(a, host, (hipStream_t)stream));
+    HIP_TRY_K(st, FS_K_COMPACT, (hipStream_t)stream, launch_kv_compact(a, host, (hipStream_t)stream));
     return FS_OK;
 }
 

@@ -21,7 +21,10 @@ FS_MAX_TREE = 1024
 FS_ARGMAX_CHUNKS = 64
 _ERR = {FS_EINVAL: "FS_EINVAL", FS_ETOPO: "FS_ETOPO", FS_ECAP: "FS_ECAP", FS_EDTYPE: "FS_EDTYPE", FS_EHIP: "FS_EHIP", FS_EWS: "FS_EWS"}
 
-EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_tree_verify_stage",
+KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "argmax", "compact")
+
+EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
+           "fs_stage_profile_end", "fs_tree_verify_stage",
            "fs_tree_logits", "fs_tree_accept", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune")
 
 
@@ -66,6 +69,8 @@ def _load():
     lib.fs_stage_workspace_bytes.argtypes = [C.POINTER(StageDesc)]
     lib.fs_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), vp, vp, vp, C.c_size_t, vp, C.POINTER(vp)]
     lib.fs_stage_destroy.argtypes = [vp]
+    lib.fs_stage_profile_begin.argtypes = [vp, ci]
+    lib.fs_stage_profile_end.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
     lib.fs_tree_verify_stage.argtypes = [vp, KVCache, ci, ci, vp, ci, ci, i32p, vp, vp]
     lib.fs_tree_logits.argtypes = [vp, vp, ci, vp, vp, vp]
     lib.fs_tree_accept.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, vp]
@@ -151,6 +156,16 @@ class Stage:
 
     def __del__(self):
         self.close()
+
+    def profile_begin(self, max_records=65536):
+        _check(_lib.fs_stage_profile_begin(self._handle, int(max_records)), "fs_stage_profile_begin")
+
+    def profile_end(self, stream=None):
+        """{kind: (total_ms, launches)} of everything the stage enqueued since profile_begin."""
+        n = len(KERNEL_KINDS)
+        ms, cnt = (C.c_double * n)(), (C.c_longlong * n)()
+        _check(_lib.fs_stage_profile_end(self._handle, _stream(stream), ms, cnt), "fs_stage_profile_end")
+        return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(KERNEL_KINDS)}
 
     def new_kv_cache(self) -> torch.Tensor:
         d = self.desc

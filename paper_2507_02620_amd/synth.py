@@ -83,8 +83,9 @@ def _gen(seed: int, tid: int, chunk: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(int(seed) << 32) | int(tid), int(chunk)]))
 
 
-def normal(seed: int, tid: int, shape, std: float = 1.0, mean: float = 0.0, threads: int = 8) -> np.ndarray:
-    """N(mean, std^2) float32 tensor; element values depend only on (seed, tid, flat index)."""
+def normal(seed: int, tid: int, shape, std: float = 1.0, mean: float = 0.0, threads: int = 8, bf16: bool = False) -> np.ndarray:
+    """N(mean, std^2) float32 tensor; element values depend only on (seed, tid, flat index).
+    bf16=True rounds every value to the nearest bfloat16 (the result stays float32)."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
     nchunk = (n + _CHUNK - 1) // _CHUNK
@@ -97,7 +98,7 @@ def normal(seed: int, tid: int, shape, std: float = 1.0, mean: float = 0.0, thre
             v *= np.float32(std)
         if mean != 0.0:
             v += np.float32(mean)
-        out[lo:hi] = v
+        out[lo:hi] = round_bf16(v) if bf16 else v
 
     if nchunk <= 1:
         for c in range(nchunk):
@@ -113,10 +114,26 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(f32_to_bf16_bits(x))
 
 
-def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+def _bits_chunk(u: np.ndarray) -> np.ndarray:
     bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
     return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def f32_to_bf16_bits(x: np.ndarray, threads: int = 8) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) of float32 values, round to nearest even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.reshape(-1).view(np.uint32)
+    n = u.shape[0]
+    if n <= _CHUNK:
+        return _bits_chunk(u).reshape(x.shape)
+    out = np.empty(n, dtype=np.uint16)
+
+    def one(c):
+        out[c * _CHUNK:(c + 1) * _CHUNK] = _bits_chunk(u[c * _CHUNK:(c + 1) * _CHUNK])
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, range((n + _CHUNK - 1) // _CHUNK)))
+    return out.reshape(x.shape)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -141,7 +158,7 @@ def layer_weights(cfg: StageConfig, layer: int, seed: int = 0) -> dict:
             out[name] = None
             continue
         mean = 1.0 if name.startswith("rms") else 0.0
-        out[name] = storage(cfg, normal(seed, TID_LAYER + 16 * layer + slot, shapes[name], 0.02, mean))
+        out[name] = normal(seed, TID_LAYER + 16 * layer + slot, shapes[name], 0.02, mean, bf16=cfg.dtype == "bf16")
     return out
 
 
@@ -149,8 +166,8 @@ def head_weights(cfg: StageConfig, seed: int = 0):
     """(final_norm [d], lm_head [vocab, d]) or (None, None) when the stage has no head."""
     if cfg.vocab <= 0:
         return None, None
-    fn = storage(cfg, normal(seed, TID_FINAL_NORM, (cfg.d_model,), 0.02, 1.0))
-    lm = storage(cfg, normal(seed, TID_LM_HEAD, (cfg.vocab, cfg.d_model), 0.02))
+    fn = normal(seed, TID_FINAL_NORM, (cfg.d_model,), 0.02, 1.0, bf16=cfg.dtype == "bf16")
+    lm = normal(seed, TID_LM_HEAD, (cfg.vocab, cfg.d_model), 0.02, bf16=cfg.dtype == "bf16")
     return fn, lm
 
 
@@ -159,14 +176,13 @@ def prefix_kv(cfg: StageConfig, layer: int, capacity: int | None = None, seed: i
     cap = cfg.kv_capacity if capacity is None else capacity
     kv = np.zeros((2, cfg.n_kv_heads, cap, cfg.head_dim), dtype=np.float32)
     if cfg.l_glo > 0:
-        pre = normal(seed, TID_PREFIX_KV + layer, (2, cfg.n_kv_heads, cfg.l_glo, cfg.head_dim))
-        kv[:, :, : cfg.l_glo, :] = storage(cfg, pre)
+        kv[:, :, : cfg.l_glo, :] = normal(seed, TID_PREFIX_KV + layer, (2, cfg.n_kv_heads, cfg.l_glo, cfg.head_dim), bf16=cfg.dtype == "bf16")
     return kv
 
 
 def hidden(cfg: StageConfig, rows: int, call: int = 0, seed: int = 0) -> np.ndarray:
     """Hidden states entering the stage for `rows` draft tokens, N(0,1)."""
-    return storage(cfg, normal(seed, TID_HIDDEN + call, (rows, cfg.d_model)))
+    return normal(seed, TID_HIDDEN + call, (rows, cfg.d_model), bf16=cfg.dtype == "bf16")
 
 
 @dataclasses.dataclass
