@@ -81,7 +81,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     std::vector<LayerPlan> layers;
     GemmPlan head;
-    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, total;
+    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, total;
 };
 
 bool valid_desc(const fs_stage_desc* d, int* err) {
@@ -98,7 +98,8 @@ bool valid_desc(const fs_stage_desc* d, int* err) {
     if (d->n_layers < 1 || d->d_model < 16 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 8 || d->vocab < 0) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->head_dim != 64 && d->head_dim != 128) return false;
-    if (d->d_model % 16 || d->d_ffn % 8) return false;
+    const int kt = d->dtype == FS_F32 ? 16 : 32;  // k-tile of the projection kernels
+    if (d->d_model % kt || d->d_ffn % kt) return false;
     if (d->kv_capacity < 1 || d->max_tree < 1 || d->max_seg < 1 || d->max_seg > FS_MAX_TREE) return false;
     if (!(d->rms_eps >= 0.f) || !(d->rope_theta > 0.f)) return false;
     return true;
@@ -146,6 +147,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.off_po = take((size_t)kMaxSplits * d->n_kv_heads * Rpad * hd * sizeof(float));
     L.off_pml = take((size_t)kMaxSplits * d->n_kv_heads * Rpad * 2 * sizeof(float));
     L.off_amw = take(M * FS_ARGMAX_CHUNKS * 2 * sizeof(int32_t));
+    L.off_invf = take((size_t)(hd / 2) * sizeof(double));
     L.total = off;
 }
 
@@ -274,6 +276,7 @@ int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, c
         launch_pack(desc->dtype, a, s);
     }
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = launch_rope_freq(st->at<double>(st->L.off_invf), hd, desc->rope_theta, s);
     if (e != hipSuccess) {
         g_last_hip = (int)e;
         delete st;
@@ -359,7 +362,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     uint64_t* anc = st->at<uint64_t>(L.off_anc);
     float2* rope = st->at<float2>(L.off_rope);
 
-    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, d.rope_theta, anc, rope, s));
+    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, st->at<double>(L.off_invf), anc, rope, s));
 
     AttnArgs at{};
     at.q = q; at.o = o; at.M = l_s; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
@@ -368,8 +371,8 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     at.stride_kv = kv.stride_kv; at.stride_head = kv.stride_head; at.stride_tok = kv.stride_tok;
     at.part_o = st->at<float>(L.off_po); at.part_ml = st->at<float>(L.off_pml);
     at.Rpad = (int)align_up((size_t)G * l_s, 16);
-    int aNW, aMTW, aRB;
-    attn_plan(st->elem, hd, l_s, G, d.n_kv_heads, at.L, kMaxSplits, &aNW, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
+    int aMTW, aRB;
+    attn_plan(st->elem, hd, l_s, G, d.n_kv_heads, at.L, kMaxSplits, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
 
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerPlan& p = L.layers[l];
@@ -384,7 +387,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         HIP_TRY_K(st, FS_K_QKV, s, launch_gemm(d.dtype, EPI_QKV, p.qkv.NT, p.qkv.NW, p.qkv.n_groups, g, s));
         // tree attention
         at.k_layer = klayer;
-        HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aNW, aMTW, aRB, s));
+        HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aMTW, aRB, s));
         // output projection + residual
         g = GemmArgs{};
         g.X = o; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;

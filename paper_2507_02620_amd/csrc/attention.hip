@@ -2,7 +2,7 @@
 //
 // Rows: the segment's M rows of the G = Hq/Hkv query heads that share one KV head are stacked into
 // R = G*M rows (rho = qh_local*M + r) so that each K/V element fetched from HBM serves all of them.
-// Grid: (KV split, KV head, row block).  A workgroup walks its slots in tiles of BS = 64: the tile's K rows
+// Grid: (KV split, KV head, row block).  A workgroup walks its slots in tiles of 64 (32 for 512-byte rows): the tile's K rows
 // are copied to LDS as they are, its V rows transposed (Vt[t][slot]) so that both MFMA operands are
 // 16-byte LDS reads.  Each wave owns MTW 16-row tiles of R:
 //     S^T = K . Q^T      (A = K fragment, rows = slots; B = Q fragment, rows = query rows)
@@ -14,13 +14,41 @@
 //
 // Visibility (tree mask): slot s is seen by row r iff s < l_glo, or bit (s - l_glo) of the row's
 // ancestor-or-self mask is set.  Tiles that lie entirely below l_glo skip the mask test.
-// With more than one split the kernel writes un-normalised partial outputs plus (max, sum) per row and
-// attn_merge_kernel combines them in split order (deterministic).
+// With more than one split each workgroup writes un-normalised partial outputs plus (max, sum) per row and
+// attn_merge_kernel combines them in split order (deterministic).  (Letting the last workgroup to arrive do
+// the merge was measured and rejected: the device-scope fences it needs write back and invalidate the whole
+// per-XCD L2 once per workgroup, several times the cost of a second launch.)
+// At least 256 threads stage a tile together and the next tile's global loads are issued before the current
+// tile is computed, so HBM latency overlaps the MFMA work.
 #include "attention.hpp"
 
 #define PADK 8   /* elements; keeps K rows 16-byte aligned and spreads LDS banks */
 #define PADV 16
 #define NEG_BIG (-1.0e30f)
+
+// Merge of the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, in split order.
+template <typename T>
+static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c) {
+    using E = Elem<T>;
+    float m = NEG_BIG;
+#pragma unroll 8
+    for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, a.part_ml[(((size_t)s * a.Hkv + kvh) * a.Rpad + rho) * 2]);
+    float den = 0.f;
+    f32x4 o{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int s = 0; s < a.n_splits; ++s) {
+        const size_t prow = ((size_t)s * a.Hkv + kvh) * a.Rpad + rho;
+        const float2 ml = *(const float2*)(a.part_ml + prow * 2);
+        const float wgt = exp2f(ml.x - m);
+        den += wgt * ml.y;
+        const f32x4 po = *(const f32x4*)(a.part_o + prow * a.hd + c * 4);
+        o += po * wgt;
+    }
+    const float inv = 1.0f / den;
+    const int qh = kvh * a.G + rho / a.M, r = rho % a.M;
+    *(typename E::out4_t*)((T*)a.o + (size_t)r * (a.Hq * a.hd) + (size_t)qh * a.hd + c * 4) =
+        E::pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
+}
 
 template <typename T, int HD, int MTW>
 __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
@@ -33,24 +61,29 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
     constexpr int NSUB = EPF / 4;     // 16-slot sub-tiles per P fragment
     constexpr int NPF = BS / (16 * NSUB);
     constexpr int KROW = HD + PADK, VROW = BS + PADV;
+    constexpr int NCC = HD / EPF;     // 16-byte chunks per K/V row
+    constexpr int CH = BS * NCC;      // chunks per tile (K and V each)
+    constexpr int CPT = CH / 256;     // chunks per thread at the smallest workgroup (256 threads)
+    static_assert(CH % 256 == 0, "tile must split evenly over 256 threads");
     __shared__ __align__(16) T Ks[BS * KROW];
     __shared__ __align__(16) T Vt[HD * VROW];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, NW = blockDim.x >> 6, nthr = blockDim.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nthr = blockDim.x;
     const int r16 = lane & 15, g = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, rb = blockIdx.z;
     const int R = a.G * a.M;
     const int ntiles = (a.L + BS - 1) / BS;
     const int t0 = split * a.tiles_per_split, t1 = min(ntiles, t0 + a.tiles_per_split);
+    // waves beyond the compute waves (or whose rows all lie beyond R) only help staging
+    const bool computes = (w < a.nwc) && ((rb * a.nwc + w) * MTW * 16 < R);
 
-    // rows of this wave
     int rho[MTW], seg_r[MTW];
     bool rok[MTW];
     frag_t qf[MTW][NKT];
 #pragma unroll
     for (int i = 0; i < MTW; ++i) {
-        rho[i] = ((rb * NW + w) * MTW + i) * 16 + r16;
-        rok[i] = rho[i] < R;
+        rho[i] = ((rb * a.nwc + w) * MTW + i) * 16 + r16;
+        rok[i] = computes && rho[i] < R;
         const int rr = rok[i] ? rho[i] : 0;
         seg_r[i] = rr % a.M;
         const int qh = kvh * a.G + rr / a.M;
@@ -71,27 +104,46 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
 
     const T* kbase = (const T*)a.k_layer + (size_t)kvh * a.stride_head;
     const T* vbase = kbase + a.stride_kv;
-    constexpr int NCC = HD / EPF;  // 16-byte chunks per row
 
+    // chunk c of a tile -> K: row-major (slot = c / NCC); V: lane -> (slot_lo, chunk part) so that the transposing
+    // LDS stores of one instruction spread over the banks
+    frag_t kreg[CPT], vreg[CPT];
+    auto fetch = [&](int tile) {
+        const int s0 = tile * BS;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            const int c = tid + i * nthr;
+            if (c < CH) {
+                const int ks = min(s0 + c / NCC, a.L - 1);  // slots beyond L re-read the last valid one; they are masked below
+                kreg[i] = *(const frag_t*)(kbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
+                const int it = c >> 6, ln = c & 63;
+                const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), a.L - 1);
+                vreg[i] = *(const frag_t*)(vbase + (size_t)vs * a.stride_tok + ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF);
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            const int c = tid + i * nthr;
+            if (c < CH) {
+                *(frag_t*)(&Ks[(c / NCC) * KROW + (c % NCC) * EPF]) = kreg[i];
+                const int it = c >> 6, ln = c & 63;
+                const int slot = (it / (NCC / 4)) * 16 + (ln & 15), col = ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF;
+#pragma unroll
+                for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = vreg[i][e];
+            }
+        }
+    };
+
+    if (t0 < t1) fetch(t0);
     for (int tile = t0; tile < t1; ++tile) {
         const int s0 = tile * BS;
         __syncthreads();  // previous tile fully consumed
-        // ---- stage K (as is) and V (transposed) ----
-        for (int c = tid; c < BS * NCC; c += nthr) {
-            const int slot = c / NCC, col = (c % NCC) * EPF;
-            frag_t f = (s0 + slot < a.L) ? *(const frag_t*)(kbase + (size_t)(s0 + slot) * a.stride_tok + col) : E::zero();
-            *(frag_t*)(&Ks[slot * KROW + col]) = f;
-        }
-        for (int c = tid; c < BS * NCC; c += nthr) {
-            // lane -> (slot_lo, chunk part) so that one store instruction spreads over the LDS banks
-            const int it = c >> 6, ln = c & 63;
-            const int ncb = NCC / 4;
-            const int slot = (it / ncb) * 16 + (ln & 15), col = ((it % ncb) * 4 + (ln >> 4)) * EPF;
-            frag_t f = (s0 + slot < a.L) ? *(const frag_t*)(vbase + (size_t)(s0 + slot) * a.stride_tok + col) : E::zero();
-#pragma unroll
-            for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = f[e];
-        }
+        stash();
         __syncthreads();
+        if (tile + 1 < t1) fetch(tile + 1);  // in flight while this tile is computed
+        if (!computes) continue;
 
         // ---- S^T = K . Q^T ----
         f32x4 st[MTW][BS / 16];
@@ -194,61 +246,41 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
     }
 }
 
-// Combine the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, in split order.
+// Combine the splits: one thread per (KV head, row, 4 head-dim elements).
 template <typename T>
-__global__ void attn_merge_kernel(const AttnArgs a) {
-    using E = Elem<T>;
+__global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     const int R = a.G * a.M, hd4 = a.hd / 4;
-    const size_t total = (size_t)a.Hkv * R * hd4;
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
-        const int c = (int)(idx % hd4);
-        const int rho = (int)((idx / hd4) % R);
-        const int kvh = (int)(idx / ((size_t)hd4 * R));
-        float m = NEG_BIG;
-        for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, a.part_ml[(((size_t)s * a.Hkv + kvh) * a.Rpad + rho) * 2]);
-        float den = 0.f;
-        f32x4 o{0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < a.n_splits; ++s) {
-            const size_t prow = ((size_t)s * a.Hkv + kvh) * a.Rpad + rho;
-            const float2 ml = *(const float2*)(a.part_ml + prow * 2);
-            const float wgt = exp2f(ml.x - m);
-            den += wgt * ml.y;
-            const f32x4 po = *(const f32x4*)(a.part_o + prow * a.hd + c * 4);
-            o += po * wgt;
-        }
-        const float inv = 1.0f / den;
-        const int qh = kvh * a.G + rho / a.M, r = rho % a.M;
-        *(typename E::out4_t*)((T*)a.o + (size_t)r * (a.Hq * a.hd) + (size_t)qh * a.hd + c * 4) =
-            E::pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
-    }
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= a.Hkv * R * hd4) return;
+    merge_row_chunk<T>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4);
 }
 
 template <typename T, int HD>
-static hipError_t launch_hd(const AttnArgs& a, int NW, int MTW, int row_blocks, hipStream_t s) {
-    dim3 grid(a.n_splits, a.Hkv, row_blocks), block(NW * 64);
+static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
+    const int nw = a.nwc < 4 ? 4 : a.nwc;  // at least 256 threads share the staging of a tile
+    dim3 grid(a.n_splits, a.Hkv, row_blocks), block(nw * 64);
     if (MTW == 1)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2>), grid, block, 0, s, a);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (a.n_splits > 1) {
-        const size_t total = (size_t)a.Hkv * a.G * a.M * (a.hd / 4);
-        int blocks = (int)((total + 255) / 256);
-        hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(blocks), dim3(256), 0, s, a);
+    if (e == hipSuccess && a.n_splits > 1) {
+        const int total = a.Hkv * a.G * a.M * (a.hd / 4);
+        hipLaunchKernelGGL(attn_merge_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, s, a);
         e = hipGetLastError();
     }
     return e;
 }
 
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NW, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split) {
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
+               int* tiles_per_split) {
     const int R = G * M, mtiles = (R + 15) / 16;
-    // up to 8 waves per workgroup, each with 1 or 2 row tiles
+    // up to 8 compute waves per workgroup, each with 1 or 2 row tiles
     int nw = mtiles < 8 ? mtiles : 8;
     int mtw = (mtiles + nw - 1) / nw > 1 ? 2 : 1;
     nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
-    *NW = nw;
+    *NWC = nw;
     *MTW = mtw;
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);
     const int BS = attn_tile_slots(elem_bytes, hd);
@@ -261,8 +293,8 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     *n_splits = (ntiles + *tiles_per_split - 1) / *tiles_per_split;
 }
 
-hipError_t launch_attention(int dtype, const AttnArgs& a, int NW, int MTW, int row_blocks, hipStream_t s) {
-    if (a.hd == 64) return dtype == 0 ? launch_hd<float, 64>(a, NW, MTW, row_blocks, s) : launch_hd<bf16_t, 64>(a, NW, MTW, row_blocks, s);
-    if (a.hd == 128) return dtype == 0 ? launch_hd<float, 128>(a, NW, MTW, row_blocks, s) : launch_hd<bf16_t, 128>(a, NW, MTW, row_blocks, s);
+hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
+    if (a.hd == 64) return dtype == 0 ? launch_hd<float, 64>(a, MTW, row_blocks, s) : launch_hd<bf16_t, 64>(a, MTW, row_blocks, s);
+    if (a.hd == 128) return dtype == 0 ? launch_hd<float, 128>(a, MTW, row_blocks, s) : launch_hd<bf16_t, 128>(a, MTW, row_blocks, s);
     return hipErrorInvalidValue;
 }

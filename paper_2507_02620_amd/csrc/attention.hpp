@@ -14,11 +14,12 @@ struct AttnArgs {
     int n_splits, tiles_per_split, Rpad;
     float* part_o;        // [n_splits][Hkv][Rpad][hd]
     float* part_ml;       // [n_splits][Hkv][Rpad][2]
+    int nwc;              // compute waves per workgroup (workgroups have at least 4 waves for staging)
 };
 
 // slots per LDS tile for a given element size and head dim
 static inline int attn_tile_slots(int elem_bytes, int hd) { return elem_bytes * hd >= 512 ? 32 : 64; }
 
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NW, int* MTW, int* row_blocks, int* n_splits,
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
                int* tiles_per_split);
-hipError_t launch_attention(int dtype, const AttnArgs& a, int NW, int MTW, int row_blocks, hipStream_t s);
+hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s);

@@ -16,7 +16,6 @@
 // workgroup reads anyway (it covers the whole K range) and applied in the epilogue.
 #include "gemm.hpp"
 
-#define PF 4 /* k-steps of loads kept in flight per wave */
 
 template <typename T>
 static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p) {
@@ -29,6 +28,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     using E = Elem<T>;
     using frag_t = typename E::frag_t;
     constexpr bool NORM = (EPI != EPI_RESID);
+    constexpr int PF = (MT + NT <= 3) ? 8 : 4;  // k-steps of loads kept in flight per wave
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, NW = blockDim.x >> 6;
     const int r16 = lane & 15, g = lane >> 4;
@@ -36,14 +36,14 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     const int row0 = mb * MT * 16;
 
     const int kt0 = (int)(((long long)a.nkt * w) / NW), kt1 = (int)(((long long)a.nkt * (w + 1)) / NW);
+    const int nsteps = kt1 - kt0;  // >= 1: the host never launches more waves than k-tiles
     const unsigned char* wbase = (const unsigned char*)a.Wp + ((size_t)grp * a.nkt) * (size_t)(NT * 1024) + (size_t)lane * 16;
+    // Rows beyond M read row M-1 instead: their results are never stored, and the loop stays free of branches.
     const T* xrow[MT];
-    bool xok[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int m = row0 + mt * 16 + r16;
-        xok[mt] = m < a.M;
-        xrow[mt] = (const T*)a.X + (size_t)(xok[mt] ? m : 0) * a.ldx + g * E::EPF;
+        const int m = min(row0 + mt * 16 + r16, a.M - 1);
+        xrow[mt] = (const T*)a.X + (size_t)m * a.ldx + g * E::EPF;
     }
 
     f32x4 acc[MT][NT];
@@ -55,35 +55,41 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // Software pipeline of PF k-steps.  Everything inside is unconditional (step indices are clamped to the
+    // wave's last k-tile, surplus steps multiply by zero) so that the loads of later steps stay in flight
+    // while earlier ones are consumed.
     frag_t bq[PF][NT], aq[PF][MT];
-    auto issue = [&](int s, int kt) {
+    auto issue = [&](int s, int step) {
+        const int kt = kt0 + min(step, nsteps - 1);
         const unsigned char* wp = wbase + (size_t)kt * (NT * 1024);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) bq[s][nt] = load_w<T>(wp + nt * 1024);
-        const int k = kt * E::KT + g * E::EPF;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const frag_t*)(xrow[mt] + (size_t)kt * E::KT);
+    };
+    auto consume = [&](int s, int step) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            // K is a multiple of EPF, so a fragment is either fully inside or fully outside the row
-            aq[s][mt] = (xok[mt] && k < a.K) ? *(const frag_t*)(xrow[mt] + (size_t)kt * E::KT) : E::zero();
+            frag_t av = aq[s][mt];
+            if (step >= nsteps) av = E::zero();
+            if (NORM) ss[mt] += E::sumsq(av);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = E::mma(bq[s][nt], av, acc[mt][nt]);
         }
     };
 #pragma unroll
-    for (int s = 0; s < PF; ++s)
-        if (kt0 + s < kt1) issue(s, kt0 + s);
-    for (int kt = kt0; kt < kt1; kt += PF) {
+    for (int s = 0; s < PF; ++s) issue(s, s);
+    const int nrounds = (nsteps + PF - 1) / PF;
+    for (int rd = 0; rd + 1 < nrounds; ++rd) {
 #pragma unroll
         for (int s = 0; s < PF; ++s) {
-            if (kt + s < kt1) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    if (NORM) ss[mt] += E::sumsq(aq[s][mt]);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = E::mma(bq[s][nt], aq[s][mt], acc[mt][nt]);
-                }
-                if (kt + s + PF < kt1) issue(s, kt + s + PF);
-            }
+            consume(s, rd * PF + s);
+            issue(s, (rd + 1) * PF + s);
+            __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its consumer: PF-1 stages stay in flight
         }
     }
+#pragma unroll
+    for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
 
     // ---- cross-wave reduction through LDS ---------------------------------------------------------
     float* red = (float*)smem;                       // [NW][MT*NT][4][64]

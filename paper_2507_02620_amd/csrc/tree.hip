@@ -7,9 +7,20 @@
 // ---- tree mask + tree position ids -> rotary table ------------------------------------------------
 // One thread per segment row walks its parent links to the root: every visited node sets one bit of the
 // row's ancestor-or-self mask, the number of links is the node's depth.  Position id = l_glo + depth.
-// The rotary table holds cos / sin of pos * theta^(-2t/hd), evaluated in fp64 and rounded once.
-__global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd, float theta,
-                                                           uint64_t* __restrict__ anc, float2* __restrict__ rope) {
+// The rotary table holds cos / sin of pos * theta^(-2t/hd): the angle is formed and reduced modulo 2*pi in fp64
+// (inverse frequencies come from a table computed once per stage), then evaluated in fp32 on [0, 2*pi).
+__global__ void rope_freq_kernel(double* __restrict__ inv_freq, int hd, float theta) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < hd / 2) inv_freq[t] = pow((double)theta, -2.0 * (double)t / (double)hd);
+}
+hipError_t launch_rope_freq(double* inv_freq, int hd, float theta, hipStream_t s) {
+    hipLaunchKernelGGL(rope_freq_kernel, dim3(1), dim3(hd / 2), 0, s, inv_freq, hd, theta);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd,
+                                                           const double* __restrict__ inv_freq, uint64_t* __restrict__ anc,
+                                                           float2* __restrict__ rope) {
     __shared__ short par[1024];
     __shared__ int pos[1024];
     const int T = seg_off + l_s;
@@ -35,14 +46,18 @@ __global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent,
     const int half = hd >> 1;
     for (int i = threadIdx.x; i < l_s * half; i += blockDim.x) {
         const int r = i / half, t = i % half;
-        const double ang = (double)pos[r] * pow((double)theta, -2.0 * (double)t / (double)hd);
-        rope[i] = make_float2((float)cos(ang), (float)sin(ang));
+        const double two_pi = 6.283185307179586476925286766559;
+        double ang = (double)pos[r] * inv_freq[t];
+        ang -= two_pi * floor(ang / two_pi);
+        float sn, cs;
+        sincosf((float)ang, &sn, &cs);
+        rope[i] = make_float2(cs, sn);
     }
 }
 
-hipError_t launch_tree_prepare(const IdxList& parent, int l_glo, int seg_off, int l_s, int hd, float theta, uint64_t* anc, float2* rope,
-                               hipStream_t s) {
-    hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, theta, anc, rope);
+hipError_t launch_tree_prepare(const IdxList& parent, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq, uint64_t* anc,
+                               float2* rope, hipStream_t s) {
+    hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope);
     return hipGetLastError();
 }
 
