@@ -72,7 +72,7 @@ void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, 
     g.NT = choose_nt(tiles, pair, max_seg, env_nt);
     g.n_groups = (tiles + g.NT - 1) / g.NT;
     g.NW = env_int("FLOWSPEC_NW", 8);
-    if (g.NW < 1 || g.NW > 8) g.NW = 8;
+    if (g.NW < 1 || g.NW > 16) g.NW = 8;
     if (g.NW > g.nkt) g.NW = g.nkt;
 }
 
@@ -134,7 +134,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
         L.head.N = d->vocab;
         L.head.wp = (void*)take(L.head.bytes());
     }
-    const size_t M = (size_t)d->max_seg;
+    const size_t M = align_up((size_t)d->max_seg, 16);  // fragment-major buffers hold whole 16-row tiles
     const int G = d->n_q_heads / d->n_kv_heads;
     const size_t Rpad = align_up((size_t)G * M, 16);
     L.off_q = take(M * nq * elem);
@@ -380,7 +380,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         const bool first = (l == 0), last = (l == d.n_layers - 1);
         // RMSNorm + QKV + RoPE + cache append
         GemmArgs g{};
-        g.X = first ? hidden_in : hb; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
+        g.X = first ? hidden_in : hb; g.x_frag = first ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
         g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
         g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
         g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
@@ -390,18 +390,18 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aMTW, aRB, s));
         // output projection + residual
         g = GemmArgs{};
-        g.X = o; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
-        g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb;
+        g.X = o; g.x_frag = 1; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
+        g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb; g.hb_frag = 1;
         HIP_TRY_K(st, FS_K_OPROJ, s, launch_gemm(d.dtype, EPI_RESID, p.o.NT, p.o.NW, p.o.n_groups, g, s));
         // RMSNorm + gate/up + SiLU * up
         g = GemmArgs{};
-        g.X = hb; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
+        g.X = hb; g.x_frag = 1; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
         HIP_TRY_K(st, FS_K_GATEUP, s, launch_gemm(d.dtype, EPI_SWIGLU, p.gu.NT, p.gu.NW, p.gu.n_groups, g, s));
         // down projection + residual
         g = GemmArgs{};
-        g.X = act; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
-        g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb;
+        g.X = act; g.x_frag = 1; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
+        g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb; g.hb_frag = last ? 0 : 1;
         HIP_TRY_K(st, FS_K_DOWN, s, launch_gemm(d.dtype, EPI_RESID, p.down.NT, p.down.NW, p.down.n_groups, g, s));
     }
     return FS_OK;

@@ -46,7 +46,7 @@ static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kv
     }
     const float inv = 1.0f / den;
     const int qh = kvh * a.G + rho / a.M, r = rho % a.M;
-    *(typename E::out4_t*)((T*)a.o + (size_t)r * (a.Hq * a.hd) + (size_t)qh * a.hd + c * 4) =
+    *(typename E::out4_t*)((T*)a.o + frag_major_index<T>(r, qh * a.hd + c * 4, a.Hq * a.hd / E::KT)) =
         E::pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
 }
 
@@ -232,10 +232,10 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         if (a.n_splits == 1) {
             const float inv = 1.0f / l;
             const int qh = kvh * a.G + rho[i] / a.M;
-            T* op = (T*)a.o + (size_t)seg_r[i] * (a.Hq * HD) + (size_t)qh * HD + g * 4;
 #pragma unroll
             for (int nt = 0; nt < NHT; ++nt)
-                *(typename E::out4_t*)(op + nt * 16) = E::pack4(acc[i][nt][0] * inv, acc[i][nt][1] * inv, acc[i][nt][2] * inv, acc[i][nt][3] * inv);
+                *(typename E::out4_t*)((T*)a.o + frag_major_index<T>(seg_r[i], qh * HD + nt * 16 + g * 4, a.Hq * HD / KT)) =
+                    E::pack4(acc[i][nt][0] * inv, acc[i][nt][1] * inv, acc[i][nt][2] * inv, acc[i][nt][3] * inv);
         } else {
             const size_t prow = ((size_t)split * a.Hkv + kvh) * a.Rpad + rho[i];
             float* po = a.part_o + prow * HD + g * 4;

@@ -6,7 +6,7 @@ struct AttnArgs {
     const void* q;        // [M][Hq*hd]
     const void* k_layer;  // K cache of this layer; V at + stride_kv
     long long stride_kv, stride_head, stride_tok;
-    void* o;              // [M][Hq*hd]
+    void* o;              // [M][Hq*hd] in fragment-major layout (operand of the output projection)
     int M, Hq, Hkv, hd, G;
     int l_glo, L;         // L = l_cache + l_s: slots [0, L) take part
     const uint64_t* anc;  // [M][FS_ANC_WORDS] ancestor-or-self masks of the segment rows (bit j = S index j)

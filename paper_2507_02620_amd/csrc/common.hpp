@@ -74,6 +74,15 @@ struct Elem<bf16_t> {
     static __device__ __forceinline__ bf16_t from_f(float v) { return (bf16_t)v; }
 };
 
+// "Fragment-major" activation layout: the [rows][K] matrix is stored as [rows/16][K/KT][64 lanes][EPF], i.e.
+// already in MFMA operand order, so that a consumer's fragment load is one contiguous KiB per wave (like the
+// re-tiled weights) instead of sixteen 64-byte row pieces.  Producers write 4 consecutive columns per lane.
+template <typename T>
+static __device__ __forceinline__ size_t frag_major_index(int m, int k, int nkt) {
+    using E = Elem<T>;
+    return ((((size_t)(m >> 4) * nkt + k / E::KT) * 64) + ((k % E::KT) / E::EPF) * 16 + (m & 15)) * E::EPF + (k % E::EPF);
+}
+
 // Small index lists that travel as kernel arguments (no device allocation, no copy, capturable).
 struct IdxList {
     int n;

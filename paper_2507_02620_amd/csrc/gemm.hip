@@ -1,9 +1,9 @@
 // Skinny-M projection kernels and the one-time weight re-tiling.
 //
 // Work decomposition: workgroup (grp, mb) owns NT consecutive 16-feature tiles ("group" grp) for the
-// MT*16 rows of row block mb.  Its NW waves split the K range; wave w streams the weight fragments
-// of k-tiles [nkt*w/NW, nkt*(w+1)/NW) — one contiguous run of NT KiB per k-tile in the re-tiled
-// layout — and multiplies them with the activation fragments of the same k-tiles (read through L2).
+// MT*16 rows of row block mb.  Its NW waves split the K range round-robin; wave w streams the weight
+// fragments of k-tiles w, w + NW, ... — NT contiguous KiB per k-tile in the re-tiled layout — and
+// multiplies them with the activation fragments of the same k-tiles (read through L2).
 // Partial 16x16 tiles are summed across waves through LDS, then the epilogue runs on the reduced tile.
 //
 // Operand roles: A = weights (rows = output features), B = activations (rows = segment rows), so the
@@ -35,15 +35,22 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     const int grp = blockIdx.x, mb = blockIdx.y;
     const int row0 = mb * MT * 16;
 
-    const int kt0 = (int)(((long long)a.nkt * w) / NW), kt1 = (int)(((long long)a.nkt * (w + 1)) / NW);
-    const int nsteps = kt1 - kt0;  // >= 1: the host never launches more waves than k-tiles
+    // k-tiles are dealt to the waves round-robin (wave w takes w, w + NW, ...): at any moment the workgroup's
+    // waves read neighbouring KiBs, so the group's weight block is swept front to back as one stream.
+    const int nsteps = (a.nkt - w + NW - 1) / NW;  // >= 1: the host never launches more waves than k-tiles
     const unsigned char* wbase = (const unsigned char*)a.Wp + ((size_t)grp * a.nkt) * (size_t)(NT * 1024) + (size_t)lane * 16;
     // Rows beyond M read row M-1 instead: their results are never stored, and the loop stays free of branches.
+    // Fragment-major activations (padded to whole 16-row tiles) are addressed like the weights.
     const T* xrow[MT];
+    const size_t xstep = a.x_frag ? (size_t)64 * E::EPF : (size_t)E::KT;  // elements between consecutive k-tiles
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int m = min(row0 + mt * 16 + r16, a.M - 1);
-        xrow[mt] = (const T*)a.X + (size_t)m * a.ldx + g * E::EPF;
+        if (a.x_frag) {
+            xrow[mt] = (const T*)a.X + (((size_t)(mb * MT + mt) * a.nkt) * 64 + lane) * E::EPF;
+        } else {
+            const int m = min(row0 + mt * 16 + r16, a.M - 1);
+            xrow[mt] = (const T*)a.X + (size_t)m * a.ldx + g * E::EPF;
+        }
     }
 
     f32x4 acc[MT][NT];
@@ -60,12 +67,12 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     // while earlier ones are consumed.
     frag_t bq[PF][NT], aq[PF][MT];
     auto issue = [&](int s, int step) {
-        const int kt = kt0 + min(step, nsteps - 1);
+        const int kt = w + min(step, nsteps - 1) * NW;
         const unsigned char* wp = wbase + (size_t)kt * (NT * 1024);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) bq[s][nt] = load_w<T>(wp + nt * 1024);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const frag_t*)(xrow[mt] + (size_t)kt * E::KT);
+        for (int mt = 0; mt < MT; ++mt) aq[s][mt] = *(const frag_t*)(xrow[mt] + (size_t)kt * xstep);
     };
     auto consume = [&](int s, int step) {
 #pragma unroll
@@ -132,7 +139,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
         }
         if (m >= a.M) continue;
         const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
-        if (EPI == EPI_RESID) {
+        if constexpr (EPI == EPI_RESID) {
             const int n = ptile * 16 + g * 4;
             if (n < a.N) {
                 float r[4];
@@ -146,14 +153,15 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
                 }
                 f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
                 *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
-                *(typename E::out4_t*)((T*)a.hb_out + (size_t)m * a.N + n) = E::pack4(h[0], h[1], h[2], h[3]);
+                const size_t hi = a.hb_frag ? frag_major_index<T>(m, n, a.N / E::KT) : (size_t)m * a.N + n;
+                *(typename E::out4_t*)((T*)a.hb_out + hi) = E::pack4(h[0], h[1], h[2], h[3]);
             }
-        } else if (EPI == EPI_LOGITS) {
+        } else if constexpr (EPI == EPI_LOGITS) {
             const int n = ptile * 16 + g * 4;
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
-        } else if (EPI == EPI_SWIGLU) {
+        } else if constexpr (EPI == EPI_SWIGLU) {
             const int f = (ptile >> 1) * 16 + g * 4;
             if (f < a.F) {
                 float o[4];
@@ -162,7 +170,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
                     float gt = rs * y[0][v], up = rs * y[1][v];
                     o[v] = gt / (1.0f + expf(-gt)) * up;
                 }
-                *(typename E::out4_t*)((T*)a.act_out + (size_t)m * a.F + f) = E::pack4(o[0], o[1], o[2], o[3]);
+                *(typename E::out4_t*)((T*)a.act_out + frag_major_index<T>(m, f, a.F / E::KT)) = E::pack4(o[0], o[1], o[2], o[3]);
             }
         } else {  // EPI_QKV
             const int tph = a.hd >> 4;  // tiles per head
@@ -209,6 +217,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
 template <typename T, int MT, int NT, int EPI>
 static hipError_t launch_one(int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
     const int mblocks = (a.M + MT * 16 - 1) / (MT * 16);
+    if (NW > 8) NW = 8;
     const size_t lds = (size_t)NW * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
     hipLaunchKernelGGL((skinny_gemm_kernel<T, MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a);
     return hipGetLastError();

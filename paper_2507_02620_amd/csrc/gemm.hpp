@@ -14,7 +14,8 @@ enum GemmEpilogue {
 enum PackKind { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
 
 struct GemmArgs {
-    const void* X;   // [M][ldx] activations, element type T
+    const void* X;   // activations, element type T: row-major [M][ldx], or fragment-major (x_frag) with K = ldx
+    int x_frag;
     const void* Wp;  // re-tiled weights: [n_groups][nkt][NT][64 lanes][16 bytes]
     int ldx, M, K, nkt;
     int N;           // valid output features (packed order)
@@ -30,9 +31,10 @@ struct GemmArgs {
     const void* resid;  // [M][N] fp32 residual stream, or T-typed stage input when resid_is_T
     int resid_is_T;
     float* h_out;  // [M][N] fp32
-    void* hb_out;  // [M][N] T
+    void* hb_out;  // [M][N] T, fragment-major if hb_frag
+    int hb_frag;
     // EPI_SWIGLU
-    void* act_out;  // [M][F]
+    void* act_out;  // [M][F] fragment-major
     int F;
     // EPI_LOGITS
     float* logits;  // [M][vocab]
