@@ -319,3 +319,35 @@ def resolve_plants(pairs, tree: Tree, vocab: int):
 
 def random_logits(rows: int, vocab: int, seed: int = 0, stream: int = 0) -> np.ndarray:
     return normal(seed, TID_LOGITS + stream, (rows, vocab))
+
+
+def extend_tree(parent: np.ndarray, token: np.ndarray, target: int, max_depth: int, max_branch: int, vocab: int, seed: int = 0,
+                stream: int = 0):
+    """Append random nodes after the retained sequence until the tree has `target` nodes (stand-in for the
+    appended segment S_app of context-aware expansion, Sec. III-D: new nodes go behind S_pr, each under an
+    existing node).  Returns (parent, token) as int32 arrays."""
+    g = _gen(seed, TID_TREE, 1_000_000 + stream)
+    par = [int(p) for p in parent]
+    tok = [int(t) for t in token]
+    dep = list(_depths(np.asarray(par, dtype=np.int32))) if par else []
+    nch = [0] * len(par)
+    sib: dict[int, set] = {}
+    for i, p in enumerate(par):
+        if p >= 0:
+            nch[p] += 1
+        sib.setdefault(p, set()).add(tok[i])
+    while len(par) < target:
+        i = len(par)
+        if i == 0:
+            par.append(-1); dep.append(0); nch.append(0); tok.append(int(g.integers(0, vocab)))
+            continue
+        ok = [j for j in range(i) if dep[j] + 1 <= max_depth and (max_branch <= 0 or nch[j] < max_branch)] or [0]
+        p = ok[int(g.integers(0, len(ok)))]
+        s = sib.setdefault(p, set())
+        while True:
+            t = int(g.integers(0, vocab))
+            if t not in s or len(s) >= vocab:
+                break
+        s.add(t)
+        par.append(p); dep.append(dep[p] + 1); nch.append(0); nch[p] += 1; tok.append(t)
+    return np.asarray(par, dtype=np.int32), np.asarray(tok, dtype=np.int32)
