@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-head", action="store_true", help="time the stage forward alone (an intermediate stage)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
+                         "traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -113,6 +116,13 @@ def main():
         stage.kv_compact(kv, l_glo, l_glo + T, retain, res=res, new_len=new_len)
         fs.seg_prune(hid_segs[-1], segs[-1][0], retain, res=res, seg_out=pr_out, l_s_out=pr_n)
 
+    if args.calibrate_copy:
+        src = torch.ones(args.calibrate_copy << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
