@@ -3,8 +3,8 @@
 // Rows: the segment's M rows of the G = Hq/Hkv query heads that share one KV head are stacked into
 // R = G*M rows (rho = qh_local*M + r) so that each K/V element fetched from HBM serves all of them.
 // Grid: (KV split, KV head, row block).  A workgroup walks its slots in tiles of 64 (32 for 512-byte rows): the tile's K rows
-// are copied to LDS as they are, its V rows transposed (Vt[t][slot]) so that both MFMA operands are
-// 16-byte LDS reads.  Each wave owns MTW 16-row tiles of R:
+// are copied to LDS as they are; V rows too for bf16 (the V^T operand is then fetched with the LDS transpose
+// load ds_read_b64_tr_b16), while f32 V rows are transposed as they are stored (Vt[t][slot]).  Each wave owns MTW 16-row tiles of R:
 //     S^T = K . Q^T      (A = K fragment, rows = slots; B = Q fragment, rows = query rows)
 //     O^T += V^T . P^T   (A = V^T fragment, rows = head-dim index; B = P fragment, rows = query rows)
 // Both products leave lane l with values of query row l % 16, so the online-softmax state (running max,
@@ -22,6 +22,8 @@
 // tile is computed, so HBM latency overlaps the MFMA work.
 #include "attention.hpp"
 
+#include <stdlib.h>
+
 #define PADK 8   /* elements; keeps K rows 16-byte aligned and spreads LDS banks */
 #define PADV 16
 #define NEG_BIG (-1.0e30f)
@@ -30,19 +32,21 @@
 template <typename T>
 static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c) {
     using E = Elem<T>;
-    float m = NEG_BIG;
-#pragma unroll 8
-    for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, a.part_ml[(((size_t)s * a.Hkv + kvh) * a.Rpad + rho) * 2]);
-    float den = 0.f;
+    // one pass with a running maximum: every load is independent of the arithmetic, so they all go out together
+    float m = NEG_BIG, den = 0.f;
     f32x4 o{0.f, 0.f, 0.f, 0.f};
+    const size_t sstride = (size_t)a.Hkv * a.Rpad;  // rows between consecutive splits
+    const float* pml = a.part_ml + ((size_t)kvh * a.Rpad + rho) * 2;
+    const float* po = a.part_o + ((size_t)kvh * a.Rpad + rho) * a.hd + c * 4;
 #pragma unroll 8
     for (int s = 0; s < a.n_splits; ++s) {
-        const size_t prow = ((size_t)s * a.Hkv + kvh) * a.Rpad + rho;
-        const float2 ml = *(const float2*)(a.part_ml + prow * 2);
-        const float wgt = exp2f(ml.x - m);
-        den += wgt * ml.y;
-        const f32x4 po = *(const f32x4*)(a.part_o + prow * a.hd + c * 4);
-        o += po * wgt;
+        const float2 ml = *(const float2*)(pml + (size_t)s * sstride * 2);
+        const f32x4 v = *(const f32x4*)(po + (size_t)s * sstride * a.hd);
+        const float mn = fmaxf(m, ml.x);
+        const float w_old = exp2f(m - mn), w_new = exp2f(ml.x - mn);
+        den = den * w_old + ml.y * w_new;
+        o = o * w_old + v * w_new;
+        m = mn;
     }
     const float inv = 1.0f / den;
     const int qh = kvh * a.G + rho / a.M, r = rho % a.M;
@@ -60,13 +64,16 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
     constexpr int NHT = HD / 16;      // 16-wide tiles of the head dim (rows of O^T)
     constexpr int NSUB = EPF / 4;     // 16-slot sub-tiles per P fragment
     constexpr int NPF = BS / (16 * NSUB);
-    constexpr int KROW = HD + PADK, VROW = BS + PADV;
+    // bf16: V is staged row-major like K and read back transposed with the LDS transpose load of gfx950;
+    // f32 (no 32-bit transpose load exists): V is transposed while it is stored.
+    constexpr bool VTR = (sizeof(T) == 2);
+    constexpr int KROW = HD + PADK, VROW = VTR ? (HD + PADK) : (BS + PADV);
     constexpr int NCC = HD / EPF;     // 16-byte chunks per K/V row
     constexpr int CH = BS * NCC;      // chunks per tile (K and V each)
     constexpr int CPT = CH / 256;     // chunks per thread at the smallest workgroup (256 threads)
     static_assert(CH % 256 == 0, "tile must split evenly over 256 threads");
     __shared__ __align__(16) T Ks[BS * KROW];
-    __shared__ __align__(16) T Vt[HD * VROW];
+    __shared__ __align__(16) T Vt[VTR ? BS * VROW : HD * VROW];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nthr = blockDim.x;
     const int r16 = lane & 15, g = lane >> 4;
@@ -116,9 +123,13 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
             if (c < CH) {
                 const int ks = min(s0 + c / NCC, a.L - 1);  // slots beyond L re-read the last valid one; they are masked below
                 kreg[i] = *(const frag_t*)(kbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
-                const int it = c >> 6, ln = c & 63;
-                const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), a.L - 1);
-                vreg[i] = *(const frag_t*)(vbase + (size_t)vs * a.stride_tok + ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF);
+                if (VTR) {
+                    vreg[i] = *(const frag_t*)(vbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
+                } else {
+                    const int it = c >> 6, ln = c & 63;
+                    const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), a.L - 1);
+                    vreg[i] = *(const frag_t*)(vbase + (size_t)vs * a.stride_tok + ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF);
+                }
             }
         }
     };
@@ -128,10 +139,14 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
             const int c = tid + i * nthr;
             if (c < CH) {
                 *(frag_t*)(&Ks[(c / NCC) * KROW + (c % NCC) * EPF]) = kreg[i];
-                const int it = c >> 6, ln = c & 63;
-                const int slot = (it / (NCC / 4)) * 16 + (ln & 15), col = ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF;
+                if (VTR) {
+                    *(frag_t*)(&Vt[(c / NCC) * VROW + (c % NCC) * EPF]) = vreg[i];
+                } else {
+                    const int it = c >> 6, ln = c & 63;
+                    const int slot = (it / (NCC / 4)) * 16 + (ln & 15), col = ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF;
 #pragma unroll
-                for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = vreg[i][e];
+                    for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = vreg[i][e];
+                }
             }
         }
     };
@@ -214,11 +229,20 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
 #pragma unroll
             for (int nt = 0; nt < NHT; ++nt) {
                 frag_t vf;
-                const T* vr = &Vt[(nt * 16 + r16) * VROW + jj * NSUB * 16 + g * 4];
+                if constexpr (VTR) {
+                    // Transpose load: within each group of 16 lanes, lane i addresses 4 consecutive head-dim elements of
+                    // slot row (i >> 2); lane j receives element j of the group's 16 columns for 4 consecutive slots.
+                    const T* vp = &Vt[(jj * NSUB * 16 + g * 4 + (r16 >> 2)) * VROW + nt * 16 + (r16 & 3) * 4];
+                    const s16x4 t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
+                    const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 16 * VROW));
+                    vf = __builtin_bit_cast(frag_t, __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7));
+                } else {
+                    const T* vr = &Vt[(nt * 16 + r16) * VROW + jj * NSUB * 16 + g * 4];
 #pragma unroll
-                for (int sub = 0; sub < NSUB; ++sub)
+                    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) vf[sub * 4 + v] = vr[sub * 16 + v];
+                        for (int v = 0; v < 4; ++v) vf[sub * 4 + v] = vr[sub * 16 + v];
+                }
 #pragma unroll
                 for (int i = 0; i < MTW; ++i) acc[i][nt] = E::mma(vf, pf[i][jj], acc[i][nt]);
             }
@@ -285,7 +309,9 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);
     const int BS = attn_tile_slots(elem_bytes, hd);
     const int ntiles = (L + BS - 1) / BS;
-    int want = (1024 + Hkv * *row_blocks - 1) / (Hkv * *row_blocks);  // about 4 workgroups per CU
+    const char* env = getenv("FLOWSPEC_ATTN_WGS");
+    const int target = env ? atoi(env) : 512;  // about 2 workgroups per CU: measured best (C2: 256-512, C5: 512)
+    int want = (target + Hkv * *row_blocks - 1) / (Hkv * *row_blocks);
     if (want > max_splits) want = max_splits;
     if (want > ntiles) want = ntiles;
     if (want < 1) want = 1;
