@@ -197,6 +197,43 @@ int fs_kv_compact(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache, const
 int fs_seg_prune(const void *seg_in, int l_s, size_t row_bytes, int off, const int32_t *retain, const fs_accept_result *res,
                  int n_retain_host, void *seg_out, int32_t *l_s_out, void *stream);
 
+/* ---- draft-stage tree bookkeeping on the host (Sec. III-B, III-C, III-D); plain CPU code, no GPU work ---------------
+ * The paper keeps the tree structure on the draft stage only and runs these steps on the CPU ("low parallelism");
+ * all arrays below are HOST arrays owned by the caller. */
+
+/*
+ * Score-based draft segmentation (Sec. III-B): T_base has n_base nodes in any topological order (parent_base[0] == -1,
+ * 0 <= parent_base[i] < i) with per-node confidences conf (the root's is taken as 1).  Cumulative scores follow Eq. 1
+ * (product along the path, in double); the L0 nodes of highest cumulative score are kept (ties: lower base index first,
+ * which keeps the selection connected) and ordered by descending score -> the draft sequence S, a topological order.
+ * Outputs, each with room for min(L0, n_base) entries: parent (S indices, parent[0] = -1), token, score, base_index.
+ * Consecutive slices of at most L_max entries of S are the draft segments.
+ * Returns the number of nodes kept, or FS_EINVAL / FS_ETOPO.
+ */
+int fs_tree_segment(const int32_t *parent_base, const int32_t *token_base, const float *conf, int n_base, int L0, int32_t *parent,
+                    int32_t *token, double *score, int32_t *base_index);
+
+/*
+ * Tree pruning on the draft stage (Sec. III-C): T_pr / S_pr from a retain list as produced by fs_tree_accept (I_acc first,
+ * then I_pr ascending): retained draft nodes keep their order, parents are renumbered by rank, the new root (n_new) gets -1.
+ * Outputs hold n_retain - n_acc entries.  Returns |S_pr| (0 when the round ended), or FS_EINVAL.
+ */
+int fs_tree_prune(const int32_t *parent, const int32_t *token, int T, const int32_t *retain, int n_acc, int n_retain,
+                  int32_t *new_parent, int32_t *new_token);
+
+/*
+ * Tree expansion by merging (Sec. III-D): T_pr (n_pr nodes, S order) and a newly drafted tree T_new (n_new nodes in descending
+ * score order, same root token).  A node of T_new whose root-to-node token path already exists in T_pr is identified with that
+ * node (the paths of T_pr are kept in a hash table keyed by (node of the parent path, token)); the other nodes, at most
+ * `limit` of them (limit < 0: all), are appended behind S_pr in T_new's order: S = S_pr || S_app.  With limit = L_se this is
+ * also the score-aware expansion (top unseen nodes of a deeper base tree).
+ * Outputs: parent / token [max_out] of the merged tree, app_src [n_app] = T_new index of each appended node,
+ * map_new [n_new] = merged index of every T_new node (-1 if it fell beyond the limit).
+ * Returns the merged size n_pr + n_app, or FS_EINVAL (root tokens differ), FS_ETOPO, FS_ECAP (max_out too small).
+ */
+int fs_tree_merge(const int32_t *parent_pr, const int32_t *token_pr, int n_pr, const int32_t *parent_new, const int32_t *token_new,
+                  int n_new, int limit, int max_out, int32_t *parent, int32_t *token, int32_t *app_src, int32_t *map_new);
+
 #ifdef __cplusplus
 }
 #endif

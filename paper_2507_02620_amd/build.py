@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflowspec_hip.so")
-SOURCES = ("api.hip", "gemm.hip", "attention.hip", "tree.hip")
+SOURCES = ("api.hip", "gemm.hip", "attention.hip", "tree.hip", "tree_host.cpp")
 EXTRA = os.environ.get("FLOWSPEC_CXXFLAGS", "").split()
 FLAGS = EXTRA + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -30,8 +30,11 @@ def build(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
 
     def one(src):
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        if src.endswith(".cpp"):  # host-only code
+            out = _run([hipcc, "-O2", "-std=c++17", "-fPIC", "-Wall", "-c", os.path.join(CSRC, src), "-o", obj])
+        else:
+            out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
         return obj

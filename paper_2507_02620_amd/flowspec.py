@@ -25,7 +25,8 @@ KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "ar
 
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
            "fs_stage_profile_end", "fs_tree_verify_stage",
-           "fs_tree_logits", "fs_tree_accept", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune")
+           "fs_tree_logits", "fs_tree_accept", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
+           "fs_tree_prune", "fs_tree_merge")
 
 
 class FlowSpecError(RuntimeError):
@@ -77,6 +78,9 @@ def _load():
     lib.fs_accept_result_to_host.argtypes = [vp, vp, ci, C.POINTER(AcceptResult), i32p, vp]
     lib.fs_kv_compact.argtypes = [vp, KVCache, ci, ci, vp, vp, ci, ci, vp, vp]
     lib.fs_seg_prune.argtypes = [vp, ci, C.c_size_t, ci, vp, vp, ci, vp, vp, vp]
+    lib.fs_tree_segment.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp, vp]
+    lib.fs_tree_prune.argtypes = [vp, vp, ci, vp, ci, ci, vp, vp]
+    lib.fs_tree_merge.argtypes = [vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp]
     for n in EXPORTS:
         if n not in ("fs_stage_workspace_bytes",):
             getattr(lib, n).restype = C.c_int
@@ -249,3 +253,46 @@ def stage_from_config(cfg, layers, final_norm=None, lm_head=None, kv_capacity=No
                  rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, kv_capacity=kv_capacity or cfg.kv_capacity,
                  max_tree=max_tree or cfg.tree_size, max_seg=max_seg or cfg.seg_len, layers=layers, final_norm=final_norm, lm_head=lm_head,
                  device=device)
+
+
+# ---- host-side tree bookkeeping (no GPU) -------------------------------------------------------------------------------
+
+def _hp(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def tree_segment(parent_base, token_base, conf, L0):
+    """Score-based draft segmentation: returns (parent, token, score, base_index) of S."""
+    pb, tb = np.ascontiguousarray(parent_base, dtype=np.int32), np.ascontiguousarray(token_base, dtype=np.int32)
+    cf = np.ascontiguousarray(conf, dtype=np.float32)
+    n = min(int(L0), pb.shape[0])
+    par, tok, sc, bi = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float64), np.zeros(n, np.int32)
+    rc = _lib.fs_tree_segment(_hp(pb), _hp(tb), _hp(cf), pb.shape[0], int(L0), _hp(par), _hp(tok), _hp(sc), _hp(bi))
+    if rc < 0:
+        raise FlowSpecError(rc, "fs_tree_segment")
+    return par[:rc], tok[:rc], sc[:rc], bi[:rc]
+
+
+def tree_prune(parent, token, retain, n_acc):
+    par, tok = np.ascontiguousarray(parent, dtype=np.int32), np.ascontiguousarray(token, dtype=np.int32)
+    ret = np.ascontiguousarray(retain, dtype=np.int32)
+    n = max(ret.shape[0] - int(n_acc), 1)
+    npar, ntok = np.zeros(n, np.int32), np.zeros(n, np.int32)
+    rc = _lib.fs_tree_prune(_hp(par), _hp(tok), par.shape[0], _hp(ret), int(n_acc), ret.shape[0], _hp(npar), _hp(ntok))
+    if rc < 0:
+        raise FlowSpecError(rc, "fs_tree_prune")
+    return npar[:rc].copy(), ntok[:rc].copy()
+
+
+def tree_merge(parent_pr, token_pr, parent_new, token_new, limit=-1, max_out=None):
+    """Merge T_new into T_pr: returns (parent, token, app_src, map_new) with S = S_pr || S_app."""
+    ppr, tpr = np.ascontiguousarray(parent_pr, dtype=np.int32), np.ascontiguousarray(token_pr, dtype=np.int32)
+    pnw, tnw = np.ascontiguousarray(parent_new, dtype=np.int32), np.ascontiguousarray(token_new, dtype=np.int32)
+    cap = int(max_out) if max_out is not None else ppr.shape[0] + pnw.shape[0]
+    par, tok = np.zeros(max(cap, 1), np.int32), np.zeros(max(cap, 1), np.int32)
+    app, mp = np.zeros(max(pnw.shape[0], 1), np.int32), np.zeros(max(pnw.shape[0], 1), np.int32)
+    rc = _lib.fs_tree_merge(_hp(ppr), _hp(tpr), ppr.shape[0], _hp(pnw), _hp(tnw), pnw.shape[0], int(limit), cap, _hp(par), _hp(tok), _hp(app),
+                            _hp(mp))
+    if rc < 0:
+        raise FlowSpecError(rc, "fs_tree_merge")
+    return par[:rc].copy(), tok[:rc].copy(), app[: rc - ppr.shape[0]].copy(), mp[: pnw.shape[0]].copy()
