@@ -402,3 +402,136 @@ int orc_num_threads(void) { return omp_get_max_threads(); }
 #else
 int orc_num_threads(void) { return 1; }
 #endif
+
+/* ---- stochastic acceptance (temperature > 0) --------------------------------------------------------------------
+ * The paper evaluates temperature 1 (Table I) with the acceptance rule of the speculative-decoding code base it
+ * extends and prints no formula (Sec. III-C).  Reading taken: sequential candidate test.  At an accepted node u with
+ * next-token distribution p_u = softmax(logits_u / temperature), the children of u are tried in S order; child c is
+ * accepted with probability p_u(token[c]) / (mass still unrejected at u); a rejected token's mass is removed.  If no
+ * child is accepted, x_new is drawn from the remaining distribution.  The emitted token is distributed exactly as p_u.
+ *
+ * To make every decision reproducible bit for bit on any machine, probabilities are integers:
+ *   z_v = logits_v * inv_temp (fp32);  m = max_v z_v;  e_v = exp2_spec((z_v - m) * log2(e));  E_v = (uint64)(e_v * 2^32)
+ *   Z = sum_v E_v (exact in 64-bit integers, any order)
+ * and decisions compare integers: accept c iff r24 * R < E_c * 2^24, R the remaining mass; residual draw: the first v
+ * whose running sum of unrejected E exceeds floor(u48 * R / 2^48).  Uniform numbers come from a counter-based
+ * generator keyed by (seed, step, draw index).  exp2_spec is a fixed sequence of IEEE fp32 operations. */
+
+static uint64_t orc_rng(uint64_t seed, uint64_t step, uint64_t k) {
+    uint64_t z = seed ^ (step * 0x9E3779B97F4A7C15ull) ^ (k * 0xBF58476D1CE4E5B9ull);
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+static uint64_t orc_exp_weight(float z, float m) {
+    const float t = (z - m) * 1.44269504088896341f;
+    if (!(t >= -64.0f)) return 0;
+    const float n = floorf(t), f = t - n;
+    float p = 1.52527338e-5f;
+    p = fmaf(p, f, 1.54035304e-4f);
+    p = fmaf(p, f, 1.33335581e-3f);
+    p = fmaf(p, f, 9.61812911e-3f);
+    p = fmaf(p, f, 5.55041087e-2f);
+    p = fmaf(p, f, 2.40226507e-1f);
+    p = fmaf(p, f, 6.93147181e-1f);
+    p = fmaf(p, f, 1.0f);
+    return (uint64_t)(ldexpf(p, (int)n) * 4294967296.0f);
+}
+
+/* Probability weights of one row: E[v] for every v; returns Z.  (Used by the tests to check the distribution.) */
+uint64_t orc_row_weights(const float *logits, int vocab, float inv_temp, uint64_t *E) {
+    float m = -INFINITY;
+    for (int v = 0; v < vocab; ++v) {
+        float z = logits[v] * inv_temp;
+        if (z > m) m = z;
+    }
+    uint64_t Z = 0;
+    for (int v = 0; v < vocab; ++v) {
+        uint64_t e = orc_exp_weight(logits[v] * inv_temp, m);
+        if (E) E[v] = e;
+        Z += e;
+    }
+    return Z;
+}
+
+int orc_accept_sample(const float *logits, int vocab, float inv_temp, const int32_t *token, const int32_t *parent, int T, int n_ver,
+                      uint64_t seed, uint64_t step, orc_accept_result *res, int32_t *retain) {
+    if (T <= 0 || n_ver < 0 || n_ver > T || vocab < 1 || !(inv_temp > 0.0f)) return ORC_EINVAL;
+    for (int i = 0; i < T; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return ORC_ETOPO;
+    if (parent[0] != -1) return ORC_ETOPO;
+    if (n_ver == 0) {
+        for (int i = 0; i < T; ++i) retain[i] = i;
+        res->n_acc = 0; res->x_new = -1; res->n_new = 0; res->continuous = 1; res->n_retain = T; res->n_pr_verified = 0;
+        return ORC_OK;
+    }
+    uint64_t *E = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)vocab);
+    char *keep = (char *)calloc((size_t)T, 1);
+    int32_t *rej = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+    uint64_t draw = 0;
+    int u = 0, n_acc = 0, x_new = -1, n_new = -1;
+    for (;;) {
+        keep[u] = 1;
+        ++n_acc;
+        const float *row = logits + (size_t)u * vocab;
+        uint64_t R = orc_row_weights(row, vocab, inv_temp, E);
+        int n_rej = 0, next = -1;
+        for (int c = u + 1; c < T && next < 0; ++c) {
+            if (parent[c] != u) continue;
+            int dup = 0;
+            for (int k = 0; k < n_rej; ++k) dup |= (rej[k] == token[c]);
+            if (dup || token[c] < 0 || token[c] >= vocab) continue;  /* already rejected here (or not a vocabulary id): no mass */
+            const uint64_t Ec = E[token[c]];
+            const uint64_t r24 = orc_rng(seed, step, draw++) >> 40;
+            if ((unsigned __int128)r24 * R < ((unsigned __int128)Ec << 24)) {
+                next = c;
+            } else {
+                R -= Ec;
+                rej[n_rej++] = token[c];
+            }
+        }
+        if (next >= 0 && next < n_ver) {  /* accepted and already verified: descend */
+            u = next;
+            continue;
+        }
+        if (next >= 0) {  /* accepted, not verified yet: it is the node n_new of the continuous condition */
+            x_new = token[next];
+            n_new = next;
+        } else {          /* every candidate rejected: draw x_new from what is left */
+            const uint64_t u48 = ((orc_rng(seed, step, draw) >> 40) << 24) | (orc_rng(seed, step, draw + 1) >> 40);
+            draw += 2;
+            const uint64_t target = (uint64_t)(((unsigned __int128)u48 * R) >> 48);
+            uint64_t run = 0;
+            x_new = vocab - 1;
+            for (int v = 0; v < vocab; ++v) {
+                int dup = 0;
+                for (int k = 0; k < n_rej; ++k) dup |= (rej[k] == v);
+                if (dup) continue;
+                run += E[v];
+                if (run > target) {
+                    x_new = v;
+                    break;
+                }
+            }
+        }
+        break;
+    }
+    int n_prv = 0;
+    if (n_new >= 0) {
+        keep[n_new] = 2;
+        for (int i = n_new + 1; i < T; ++i)
+            if (parent[i] >= 0 && keep[parent[i]] == 2) keep[i] = 2;
+        for (int i = 0; i < n_ver; ++i) n_prv += (keep[i] == 2);
+    }
+    int n = 0;
+    for (int i = 0; i < T; ++i)
+        if (keep[i] == 1) retain[n++] = i;
+    for (int i = 0; i < T; ++i)
+        if (keep[i] == 2) retain[n++] = i;
+    res->n_acc = n_acc; res->x_new = x_new; res->n_new = n_new; res->continuous = (n_new >= 0);
+    res->n_retain = n; res->n_pr_verified = n_prv;
+    free(E); free(keep); free(rej);
+    return ORC_OK;
+}

@@ -19,7 +19,8 @@ _LIB = os.path.join(_HERE, "libflowspec_oracle.so")
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (AVX2-level code so the library also runs on the GPU host)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=gnu11", "-Wall", "-o", _LIB, _SRC,
+               "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -195,3 +196,23 @@ def seg_prune(seg, off, retain):
     row = seg.itemsize * int(np.prod(seg.shape[1:]))
     n = lib().orc_seg_prune(_ptr(seg), seg.shape[0], C.c_size_t(row), int(off), _ptr(retain), retain.shape[0], _ptr(out))
     return out[:n].copy()
+
+
+def row_weights(logits_row, inv_temp):
+    """Integer probability weights E[v] of one row and their sum Z (the sampling distribution is E / Z)."""
+    row = np.ascontiguousarray(logits_row, dtype=np.float32)
+    E = np.zeros(row.shape[0], dtype=np.uint64)
+    lib().orc_row_weights.restype = C.c_uint64
+    Z = lib().orc_row_weights(_ptr(row), row.shape[0], C.c_float(inv_temp), _ptr(E))
+    return E, int(Z)
+
+
+def accept_sample(logits, inv_temp, token, parent, n_ver, seed, step):
+    token, parent = _i32(token), _i32(parent)
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T = token.shape[0]
+    res = AcceptResult()
+    retain = np.full(T, -1, dtype=np.int32)
+    _check(lib().orc_accept_sample(_ptr(logits), logits.shape[1], C.c_float(inv_temp), _ptr(token), _ptr(parent), T, int(n_ver),
+                                   C.c_uint64(seed), C.c_uint64(step), C.byref(res), _ptr(retain)), "orc_accept_sample")
+    return res, retain[: res.n_retain].copy()

@@ -1,0 +1,103 @@
+"""Pins for the stochastic (temperature > 0) acceptance oracle.  CPU only."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2507_02620_amd import synth
+
+
+def test_integer_weights_are_the_softmax():
+    rng = np.random.default_rng(0)
+    for temp in (1.0, 0.7, 2.5):
+        lg = (rng.standard_normal(5000) * 3).astype(np.float32)
+        E, Z = oracle.row_weights(lg, 1.0 / temp)
+        ref = torch.softmax(torch.tensor(lg, dtype=torch.float64) / temp, dim=0).numpy()
+        np.testing.assert_allclose(E / Z, ref, rtol=2e-6, atol=1e-9)
+        assert int(E.sum()) == Z and E.max() <= (1 << 32)
+
+
+def _emitted(lg, token, parent, n_ver, n_draws, inv_temp=1.0, seed=11):
+    out = []
+    for step in range(n_draws):
+        res, retain = oracle.accept_sample(lg, inv_temp, token, parent, n_ver, seed, step)
+        out.append((res.n_acc, res.x_new, res.n_new, res.continuous, tuple(retain)))
+    return out
+
+
+def test_emitted_token_follows_the_target_distribution():
+    """Root with three candidate children (none verified): whatever the candidates are, the token that leaves the step —
+    an accepted candidate or the residual draw — must be distributed as softmax(logits of the root)."""
+    vocab = 12
+    rng = np.random.default_rng(3)
+    lg = rng.standard_normal((1, vocab)).astype(np.float32) * 1.5
+    p = torch.softmax(torch.tensor(lg[0], dtype=torch.float64), 0).numpy()
+    parent = np.array([-1, 0, 0, 0], dtype=np.int32)
+    token = np.array([5, 2, 7, 9], dtype=np.int32)
+    N = 40000
+    draws = _emitted(lg, token, parent, 1, N)
+    counts = np.bincount([d[1] for d in draws], minlength=vocab)
+    # 5-sigma binomial band per token
+    sigma = np.sqrt(N * p * (1 - p))
+    assert (np.abs(counts - N * p) < 5 * sigma + 1).all(), (counts / N, p)
+    for n_acc, x_new, n_new, cont, retain in draws[:2000]:
+        assert n_acc == 1
+        if x_new in (2, 7, 9):
+            assert cont == 1 and token[n_new] == x_new and retain == (0, n_new)
+        else:
+            assert cont == 0 and n_new == -1 and retain == (0,)
+
+
+def test_acceptance_probability_of_a_verified_chain():
+    """Chain 0 -> 1 -> 2, all verified: P(n_acc >= 2) = p_0(token[1]); P(n_acc = 3) = p_0(token[1]) * p_1(token[2])."""
+    vocab = 6
+    lg = np.array([[0.0, 1.0, 0.5, -1.0, 0.2, 0.3], [1.0, 0.0, 2.0, 0.1, 0.1, 0.1], [0.0] * 6], dtype=np.float32)
+    parent = np.array([-1, 0, 1], dtype=np.int32)
+    token = np.array([4, 1, 2], dtype=np.int32)
+    p0 = torch.softmax(torch.tensor(lg[0], dtype=torch.float64), 0).numpy()
+    p1 = torch.softmax(torch.tensor(lg[1], dtype=torch.float64), 0).numpy()
+    N = 30000
+    draws = _emitted(lg, token, parent, 3, N)
+    n_acc = np.array([d[0] for d in draws])
+    q2, q3 = p0[1], p0[1] * p1[2]
+    assert abs((n_acc >= 2).mean() - q2) < 5 * np.sqrt(q2 * (1 - q2) / N)
+    assert abs((n_acc == 3).mean() - q3) < 5 * np.sqrt(q3 * (1 - q3) / N)
+    # a rejected candidate's token can never be the residual draw at that node
+    assert all(not (d[0] == 1 and d[1] == 1) for d in draws)
+
+
+def test_low_temperature_limit_is_greedy():
+    rng = np.random.default_rng(5)
+    for seed in range(8):
+        tree = synth.random_tree(30, 5, 3, 40, seed)
+        n_ver = int(rng.integers(1, 31))
+        lg = synth.random_logits(n_ver, 40, seed, 1)
+        for r, t in synth.resolve_plants(synth.plant_path(tree, n_ver, seed, 0, 0.3, 2.0), tree, 40):
+            lg[r, t] += 30.0
+        g_res, g_ret = oracle.accept(oracle.argmax_rows(lg), tree.token, tree.parent, n_ver)
+        s_res, s_ret = oracle.accept_sample(lg, 50.0, tree.token, tree.parent, n_ver, 1, seed)   # temperature 0.02
+        assert s_res.as_tuple() == g_res.as_tuple() and np.array_equal(s_ret, g_ret)
+
+
+def test_structure_and_edge_cases():
+    tree = synth.random_tree(25, 5, 3, 9, 2)
+    lg = synth.random_logits(25, 9, 2, 2)
+    for step in range(200):
+        n_ver = 1 + step % 25
+        res, retain = oracle.accept_sample(lg[:n_ver], 1.0, tree.token, tree.parent, n_ver, 7, step)
+        assert res.n_acc >= 1 and (np.diff(retain) > 0).all() and retain[0] == 0
+        acc = retain[: res.n_acc]
+        assert all(tree.parent[acc[k]] == acc[k - 1] for k in range(1, len(acc)))      # I_acc is a root path
+        if res.continuous:
+            assert res.n_new >= n_ver and tree.parent[res.n_new] == acc[-1] and tree.token[res.n_new] == res.x_new
+            assert res.n_pr_verified == 0
+        else:
+            assert res.n_retain == res.n_acc and 0 <= res.x_new < 9
+    res, retain = oracle.accept_sample(lg[:1], 1.0, tree.token, tree.parent, 0, 7, 0)
+    assert res.as_tuple() == (0, -1, 0, 1, 25, 0)
+    with pytest.raises(oracle.OracleError):
+        oracle.accept_sample(lg, 0.0, tree.token, tree.parent, 3, 7, 0)
+    # same key -> same result; different step -> eventually different
+    a = [oracle.accept_sample(lg, 1.0, tree.token, tree.parent, 25, 9, s)[0].as_tuple() for s in range(50)]
+    b = [oracle.accept_sample(lg, 1.0, tree.token, tree.parent, 25, 9, s)[0].as_tuple() for s in range(50)]
+    assert a == b and len(set(a)) > 1
