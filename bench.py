@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-head", action="store_true", help="time the stage forward alone (an intermediate stage)")
+    ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -99,6 +100,8 @@ def main():
     plants = synth.resolve_plants(synth.plant_path(tree, T, seed, 0, p_stop=0.0, mean_extra=2.0), tree, max(cfg.vocab, 2))
     plant_rows = torch.tensor([r for r, _ in plants], dtype=torch.long, device=dev)
     plant_toks = torch.tensor([t for _, t in plants], dtype=torch.long, device=dev)
+    swork = torch.empty(32 + 12 * T, dtype=torch.uint8, device=dev)
+    step_no = [0]
     setup_s = time.time() - t_setup
 
     def step():
@@ -109,7 +112,11 @@ def main():
                 stage.tree_logits(out_segs[i], logits[off:off + n], amax[off:off + n])
         if use_head:
             logits[plant_rows, plant_toks] += 100.0  # planted acceptance (stand-in for a trained draft model's hit rate)
-            fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work)
+            if args.temperature > 0:
+                fs.tree_accept_sample(logits, args.temperature, token_d, parent_d, T, seed, step_no[0], res, retain, swork)
+                step_no[0] += 1
+            else:
+                fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work)
         else:
             amax[plant_rows] = plant_toks.to(torch.int32)
             fs.tree_accept(None, amax, token_d, parent_d, T, res, retain, work)
@@ -164,7 +171,8 @@ def main():
         "config": {"workload": cfg.name, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
                    "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv x {cfg.head_dim}", "d_ffn": cfg.d_ffn, "vocab": cfg.vocab if use_head else 0,
                    "kv_prefix": cfg.l_glo, "tree_nodes": T, "segment": cfg.seg_len, "segments_per_step": len(segs),
-                   "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs)},
+                   "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs),
+                   "acceptance": "greedy" if args.temperature <= 0 else "sampled, temperature %g" % args.temperature},
         "roofline": {"kernel": "skinny_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,

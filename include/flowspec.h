@@ -169,6 +169,22 @@ typedef struct {
 int fs_tree_accept(const float *logits, int32_t *amax, int vocab, const int32_t *token, const int32_t *parent, int T, int n_ver,
                    fs_accept_result *res, int32_t *retain, int32_t *work, void *stream);
 
+/*
+ * Stochastic acceptance at a temperature > 0 (the paper's temperature-1 runs, Table I; Sec. III-C gives no formula).
+ * Reading taken: sequential candidate test.  At an accepted node u with p = softmax(logits_u / temperature) the children of
+ * u are tried in S order; a child is accepted with probability p(token) / (mass not yet rejected at u); a rejected token's
+ * mass is struck.  An accepted verified child continues the walk; an accepted unverified child is n_new (continuous);
+ * if every child is rejected x_new is drawn from what is left.  The token leaving the step is distributed exactly as p.
+ * Probabilities are 64-bit integer weights E_v = (uint64)(exp2_spec((z_v - max z) * log2 e) * 2^32), z_v = logits_v *
+ * (1/temperature) in fp32, with exp2_spec a fixed sequence of IEEE fp32 operations, and uniform numbers come from a
+ * counter-based generator keyed by (seed, step, draw index): every decision is an integer comparison, reproducible bit for
+ * bit.  Outputs as fs_tree_accept.
+ *   logits device fp32 [n_ver, vocab];  work device, 16-byte aligned, >= 16 + 12 * n_ver bytes
+ * Errors: FS_EINVAL, FS_ECAP, FS_EHIP.
+ */
+int fs_tree_accept_sample(const float *logits, int vocab, float temperature, const int32_t *token, const int32_t *parent, int T,
+                          int n_ver, uint64_t seed, uint64_t step, fs_accept_result *res, int32_t *retain, void *work, void *stream);
+
 /* Copies the result and the first n_retain entries of retain to the host and waits for the stream: the one
  * synchronisation point of the path.  retain_host must hold T entries. */
 int fs_accept_result_to_host(const fs_accept_result *res_dev, const int32_t *retain_dev, int T, fs_accept_result *res_host,

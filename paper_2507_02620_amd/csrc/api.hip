@@ -437,6 +437,19 @@ int fs_tree_accept(const float* logits, int32_t* amax, int vocab, const int32_t*
     return FS_OK;
 }
 
+int fs_tree_accept_sample(const float* logits, int vocab, float temperature, const int32_t* token, const int32_t* parent, int T, int n_ver,
+                          uint64_t seed, uint64_t step, fs_accept_result* res, int32_t* retain, void* work, void* stream) {
+    if (!token || !parent || !res || !retain || T < 1 || n_ver < 0 || n_ver > T) return FS_EINVAL;
+    if (T > FS_MAX_TREE) return FS_ECAP;
+    if (!(temperature > 0.f) || vocab < 1) return FS_EINVAL;
+    if (n_ver > 0 && (!logits || !work || ((uintptr_t)work & 15))) return FS_EINVAL;
+    const float inv_temp = 1.0f / temperature;
+    if (!(inv_temp > 0.f)) return FS_EINVAL;
+    HIP_TRY(launch_accept_sample(logits, vocab, inv_temp, token, parent, T, n_ver, seed, step, (AcceptResultDev*)res, retain, work,
+                                 (hipStream_t)stream));
+    return FS_OK;
+}
+
 int fs_accept_result_to_host(const fs_accept_result* res_dev, const int32_t* retain_dev, int T, fs_accept_result* res_host, int32_t* retain_host,
                              void* stream) {
     if (!res_dev || !res_host || T < 0) return FS_EINVAL;

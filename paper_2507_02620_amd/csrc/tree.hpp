@@ -23,6 +23,8 @@ hipError_t launch_tree_prepare(const IdxList& parent, int l_glo, int seg_off, in
 hipError_t launch_argmax(const float* logits, int rows, int vocab, int chunks, int32_t* work, int32_t* amax, hipStream_t s);
 hipError_t launch_accept(const int32_t* amax, const int32_t* token, const int32_t* parent, int T, int n_ver, AcceptResultDev* res,
                          int32_t* retain, hipStream_t s);
+hipError_t launch_accept_sample(const float* logits, int vocab, float inv_temp, const int32_t* token, const int32_t* parent, int T, int n_ver,
+                                uint64_t seed, uint64_t step, AcceptResultDev* res, int32_t* retain, void* work, hipStream_t s);
 hipError_t launch_kv_compact(const CompactArgs& a, const IdxList& host, hipStream_t s);
 hipError_t launch_seg_prune(const void* seg_in, int l_s, size_t row_bytes, int off, const int32_t* retain_dev, const AcceptResultDev* res_dev,
                             const IdxList& host, void* seg_out, int32_t* l_s_out, hipStream_t s);
