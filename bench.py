@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-head", action="store_true", help="time the stage forward alone (an intermediate stage)")
+    ap.add_argument("--weights", default="dense", choices=["dense", "int4"],
+                    help="int4: 4-bit group weights with bf16 activations (W4A16, the paper's 13B setting); bf16 workloads only")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
@@ -71,14 +73,23 @@ def main():
     use_head = cfg.vocab > 0 and not args.no_head
 
     t_setup = time.time()
-    host_layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
-    fn, lm = synth.head_weights(cfg, seed) if use_head else (None, None)
+    w4 = args.weights == "int4"
     up = lambda a: None if a is None else torch.from_numpy(a).to(dev, tdt)
-    dev_layers = [{k: up(v) for k, v in lw.items()} for lw in host_layers]
-    dfn, dlm = up(fn), up(lm)
-    stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm)
+    if w4:
+        host_layers = [synth.layer_weights_w4(cfg, l, seed) for l in range(cfg.n_layers)]
+        fn, lm, lm_scale = synth.head_weights_w4(cfg, seed) if use_head else (None, None, None)
+        codes = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+        dev_layers = [{k: (codes(v) if v is not None and v.dtype == np.uint8 else up(v)) for k, v in lw.items()} for lw in host_layers]
+        dfn, dlm, dls = up(fn), codes(lm), up(lm_scale)
+        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm, lm_head_scale=dls, weight_format=fs.FS_WFMT_INT4_G128)
+    else:
+        host_layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
+        fn, lm = synth.head_weights(cfg, seed) if use_head else (None, None)
+        dev_layers = [{k: up(v) for k, v in lw.items()} for lw in host_layers]
+        dfn, dlm, dls = up(fn), up(lm), None
+        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm)
     torch.cuda.synchronize()
-    del dev_layers, dfn, dlm
+    del dev_layers, dfn, dlm, dls
     torch.cuda.empty_cache()
     kv = stage.new_kv_cache()
     for l in range(cfg.n_layers):
@@ -142,23 +153,24 @@ def main():
     tok_s = T * args.steps / dt
 
     # second pass of the same steps with the per-kernel event timers armed
-    stage.profile_begin(args.steps * (len(segs) * (2 + 6 * cfg.n_layers) + 4) + 16)
+    stage.profile_begin(args.steps * (len(segs) * (5 + 6 * cfg.n_layers) + 4) + 16)
     for _ in range(args.steps):
         step()
     prof = stage.profile_end()
     out_res, out_ret = fs.accept_result_to_host(res, retain, T)
 
     elem = 4 if cfg.dtype == "f32" else 2
-    gu_bytes = 2 * cfg.d_ffn * cfg.d_model * elem          # gate + up weights, streamed once per launch
+    welem = (0.5 + 2.0 / 128) if w4 else elem                 # weight bytes per parameter (4-bit code + a bf16 scale per 128)
+    gu_bytes = int(2 * cfg.d_ffn * cfg.d_model * welem)       # gate + up weights, streamed once per launch
     gu_ms, gu_n = prof["gateup"]
     gu_avg_ms = gu_ms / max(gu_n, 1)
     achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9 if gu_n else 0.0
     kern = {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1]} for k, v in prof.items() if v[1]}
     stage_weight_bytes = cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model + 2 * cfg.n_kv_heads * cfg.head_dim * cfg.d_model
-                                         + 3 * cfg.d_ffn * cfg.d_model) * elem
-    head_bytes = cfg.vocab * cfg.d_model * elem if use_head else 0
+                                         + 3 * cfg.d_ffn * cfg.d_model) * welem
+    head_bytes = cfg.vocab * cfg.d_model * welem if use_head else 0
     kv_bytes = cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * elem * sum(cfg.l_glo + o + n for o, n in segs)
-    step_bytes = len(segs) * (stage_weight_bytes + head_bytes) + kv_bytes
+    step_bytes = int(len(segs) * (stage_weight_bytes + head_bytes) + kv_bytes)
 
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
@@ -168,15 +180,15 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
+        "config": {"workload": cfg.name + ("-w4a16" if w4 else ""), "weights": "int4 codes, bf16 scale per 128 columns" if w4 else cfg.dtype, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
                    "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv x {cfg.head_dim}", "d_ffn": cfg.d_ffn, "vocab": cfg.vocab if use_head else 0,
                    "kv_prefix": cfg.l_glo, "tree_nodes": T, "segment": cfg.seg_len, "segments_per_step": len(segs),
                    "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs),
                    "acceptance": "greedy" if args.temperature <= 0 else "sampled, temperature %g" % args.temperature},
-        "roofline": {"kernel": "skinny_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)", "bound": "hbm",
+        "roofline": {"kernel": "skinny_gemm%s_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)" % ("_w4" if w4 else ""), "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
-                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower()))},
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))},
         "whole_step": {"algorithmic_bytes": step_bytes, "achieved_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "kernels": kern,
@@ -187,9 +199,12 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle  # cpu_baseline leg: the oracle as it stands, timed on the host cores
         bits = lambda a: None if a is None else synth.f32_to_bf16_bits(a)
-        wl = host_layers if cfg.dtype == "f32" else [{k: bits(v) for k, v in lw.items()} for lw in host_layers]
-        ost = oracle.Stage(cfg, wl, fn if cfg.dtype == "f32" else bits(fn), lm if cfg.dtype == "f32" else bits(lm), None,
-                           bf16_bits=cfg.dtype != "f32")
+        if w4:  # the oracle runs on the plain matrices the codes stand for
+            ost = oracle.Stage(cfg, [oracle.dequant_layer(lw) for lw in host_layers], fn, None if lm is None else oracle.dequant_w4(lm, lm_scale))
+        else:
+            wl = host_layers if cfg.dtype == "f32" else [{k: bits(v) for k, v in lw.items()} for lw in host_layers]
+            ost = oracle.Stage(cfg, wl, fn if cfg.dtype == "f32" else bits(fn), lm if cfg.dtype == "f32" else bits(lm), None,
+                               bf16_bits=cfg.dtype != "f32")
         for l in range(cfg.n_layers):
             ost.load_prefix(l, synth.prefix_kv(cfg, l, None, seed))
         hs = synth.hidden(cfg, T, 0, seed)

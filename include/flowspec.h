@@ -46,6 +46,13 @@ extern "C" {
 #define FS_F32 0
 #define FS_BF16 1
 
+/* weight formats (fs_stage_desc.weight_format) */
+#define FS_WFMT_DENSE 0     /* weights of element type dtype */
+#define FS_WFMT_INT4_G128 1 /* W4A16 (the paper's 13B setting, Sec. IV-A / Appendix): 4-bit codes + bf16 scales per 128 input columns,
+                               w[n][k] = scale[n][k/128] * (code[n][k] - 8); activations, KV cache and arithmetic stay bf16 / fp32.
+                               Each weight pointer is a uint8 [out, in/2] array (column k even in the low nibble) and each scale pointer
+                               a bf16 [out, in/128] array; d_model, d_ffn and n_q_heads*head_dim must be multiples of 128. */
+
 #define FS_MAX_TREE 1024 /* largest draft tree (nodes of S) any entry point accepts */
 
 /* Shape of a stage (decoder form per Appendix A and the LLaMA2 / Qwen2 models of Sec. IV-A). */
@@ -58,12 +65,14 @@ typedef struct {
     int kv_capacity; /* slots per head of the KV cache the stage will be used with */
     int max_tree;    /* largest T (<= FS_MAX_TREE) */
     int max_seg;     /* largest segment length l_s (the paper's L_max) */
+    int weight_format; /* FS_WFMT_DENSE | FS_WFMT_INT4_G128 (requires dtype == FS_BF16) */
 } fs_stage_desc;
 
 /* One layer's tensors, device, row-major [out, in], element type desc.dtype.  Biases may be NULL. */
 typedef struct {
     const void *rms_attn, *wq, *wk, *wv, *wo, *rms_ffn, *w_gate, *w_up, *w_down;
     const void *bq, *bk, *bv;
+    const void *sq, *sk, *sv, *so, *s_gate, *s_up, *s_down; /* FS_WFMT_INT4_G128 only: scales of the seven matrices */
 } fs_layer_weights;
 
 /* KV cache, device, element type desc.dtype.  Element (layer, kv, head, slot, t) is at
@@ -83,13 +92,14 @@ size_t fs_stage_workspace_bytes(const fs_stage_desc *desc);
 /*
  * Create a stage: validates the shape, re-tiles the weights into the workspace (kernels on `stream`).
  *   layers      host array [n_layers] of device pointers
- *   final_norm  device [d_model], lm_head device [vocab, d_model]; both required iff desc->vocab > 0
+ *   final_norm  device [d_model], lm_head device [vocab, d_model] (codes for 4-bit weights); both required iff desc->vocab > 0
  *   workspace   device, 256-byte aligned, >= fs_stage_workspace_bytes(desc); owned by the caller and must
  *               outlive the stage
  * Errors: FS_EINVAL, FS_EDTYPE, FS_ECAP (max_tree > FS_MAX_TREE), FS_EWS, FS_EHIP.
  */
 int fs_stage_create(const fs_stage_desc *desc, const fs_layer_weights *layers, const void *final_norm, const void *lm_head,
-                    void *workspace, size_t workspace_bytes, void *stream, fs_stage **out);
+                    const void *lm_head_scale /* FS_WFMT_INT4_G128 with a head, else NULL */, void *workspace, size_t workspace_bytes,
+                    void *stream, fs_stage **out);
 int fs_stage_destroy(fs_stage *stage);
 
 /*

@@ -104,6 +104,29 @@ def rope(v, pos, theta):
     return v
 
 
+W4_SCALES = {"wq": "sq", "wk": "sk", "wv": "sv", "wo": "so", "w_gate": "s_gate", "w_up": "s_up", "w_down": "s_down"}
+
+
+def dequant_w4(codes, scales):
+    """4-bit group storage to plain weights: w[n][k] = scale[n][k // 128] * (code[n][k] - 8), column k even in the low
+    nibble of byte k // 2.  The product of a bf16 scale and an integer in [-8, 7] is exact in float32."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    n, half = codes.shape
+    q = np.empty((n, half, 2), dtype=np.int16)
+    q[:, :, 0] = codes & 15
+    q[:, :, 1] = codes >> 4
+    q = (q.reshape(n, half * 2 // 128, 128) - 8).astype(np.float32)
+    return np.ascontiguousarray((q * np.asarray(scales, dtype=np.float32)[:, :, None]).reshape(n, half * 2))
+
+
+def dequant_layer(lw):
+    """A layer dict with 4-bit matrices (codes + s* scales) as plain float32 matrices."""
+    out = {k: v for k, v in lw.items() if k not in W4_SCALES.values()}
+    for name, sname in W4_SCALES.items():
+        out[name] = dequant_w4(lw[name], lw[sname])
+    return out
+
+
 class Stage:
     """Oracle-side state of one stage: weights (float32 arrays, or uint16 bf16 bit patterns) and a fp64 KV cache."""
 

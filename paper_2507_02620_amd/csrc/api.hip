@@ -37,9 +37,11 @@ namespace {
 
 struct GemmPlan {
     void* wp = nullptr;
+    void* sp = nullptr;  // 4-bit: scales
     float* bias = nullptr;
-    int N = 0, K = 0, nkt = 0, NT = 1, NW = 8, n_groups = 0;
-    size_t bytes() const { return (size_t)n_groups * nkt * NT * 1024; }
+    int N = 0, K = 0, nkt = 0, NT = 1, NW = 8, n_groups = 0, w4 = 0;
+    size_t bytes() const { return w4 ? (size_t)n_groups * (nkt / 4) * NT * 1024 : (size_t)n_groups * nkt * NT * 1024; }
+    size_t scale_bytes() const { return w4 ? (size_t)n_groups * (nkt / 4) * NT * 16 * 2 : 0; }
 };
 
 struct LayerPlan {
@@ -65,15 +67,28 @@ int choose_nt(int tiles, bool pair, int max_seg, const char* env) {
     return nt;
 }
 
-void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, const char* env_nt) {
+void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, const char* env_nt, int w4 = 0) {
     const int KT = 64 / elem;  // 32 for bf16, 16 for f32
     g.K = K;
+    g.w4 = w4;
     g.nkt = (K + KT - 1) / KT;
     g.NT = choose_nt(tiles, pair, max_seg, env_nt);
+    if (w4) {
+        // a 4-bit tile is a quarter of the bytes: larger groups keep the per-workgroup stream long enough;
+        // 64-row segments stay at NT <= 2 (registers)
+        int nt = pair ? 2 : 1;
+        if (tiles / 4 >= 256 && max_seg <= 32) nt = 4;
+        else if (tiles / 2 >= 128) nt = 2;
+        const int o = env_int(env_nt, 0);
+        if (o == 1 || o == 2 || o == 4) nt = (pair && o == 1) ? 2 : o;
+        if (max_seg > 32 && nt > 2) nt = 2;
+        g.NT = nt;
+    }
     g.n_groups = (tiles + g.NT - 1) / g.NT;
     g.NW = env_int("FLOWSPEC_NW", 8);
     if (g.NW < 1 || g.NW > 16) g.NW = 8;
-    if (g.NW > g.nkt) g.NW = g.nkt;
+    const int ksteps = w4 ? g.nkt / 4 : g.nkt;
+    if (g.NW > ksteps) g.NW = ksteps;
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -81,7 +96,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     std::vector<LayerPlan> layers;
     GemmPlan head;
-    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, total;
+    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, off_gain, off_sspa, off_sspb, total;
+    int ssp_stride;
 };
 
 bool valid_desc(const fs_stage_desc* d, int* err) {
@@ -98,7 +114,16 @@ bool valid_desc(const fs_stage_desc* d, int* err) {
     if (d->n_layers < 1 || d->d_model < 16 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 8 || d->vocab < 0) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->head_dim != 64 && d->head_dim != 128) return false;
-    const int kt = d->dtype == FS_F32 ? 16 : 32;  // k-tile of the projection kernels
+    int kt = d->dtype == FS_F32 ? 16 : 32;  // k-tile of the projection kernels
+    if (d->weight_format != FS_WFMT_DENSE && d->weight_format != FS_WFMT_INT4_G128) return false;
+    if (d->weight_format == FS_WFMT_INT4_G128) {
+        if (d->dtype != FS_BF16) {
+            *err = FS_EDTYPE;
+            return false;
+        }
+        kt = 128;  // one scale per 128 input columns
+        if ((d->n_q_heads * d->head_dim) % kt) return false;
+    }
     if (d->d_model % kt || d->d_ffn % kt) return false;
     if (d->kv_capacity < 1 || d->max_tree < 1 || d->max_seg < 1 || d->max_seg > FS_MAX_TREE) return false;
     if (!(d->rms_eps >= 0.f) || !(d->rope_theta > 0.f)) return false;
@@ -114,25 +139,30 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
         off = align_up(off + bytes, 256);
         return o;
     };
+    const int w4 = d->weight_format == FS_WFMT_INT4_G128;
     L.layers.resize(d->n_layers);
     for (int l = 0; l < d->n_layers; ++l) {
         LayerPlan& p = L.layers[l];
         const int qkv_tiles = (d->n_q_heads + 2 * d->n_kv_heads) * hd / 16;
-        plan_gemm(p.qkv, qkv_tiles, d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_QKV");
+        plan_gemm(p.qkv, qkv_tiles, d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_QKV", w4);
         p.qkv.N = qkv_tiles * 16;
-        plan_gemm(p.o, d->d_model / 16, nq, elem, false, d->max_seg, "FLOWSPEC_NT_O");
+        plan_gemm(p.o, d->d_model / 16, nq, elem, false, d->max_seg, "FLOWSPEC_NT_O", w4);
         p.o.N = d->d_model;
-        plan_gemm(p.gu, 2 * ((d->d_ffn + 15) / 16), d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_GU");
+        plan_gemm(p.gu, 2 * ((d->d_ffn + 15) / 16), d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_GU", w4);
         p.gu.N = d->d_ffn;
-        plan_gemm(p.down, d->d_model / 16, d->d_ffn, elem, false, d->max_seg, "FLOWSPEC_NT_DOWN");
+        plan_gemm(p.down, d->d_model / 16, d->d_ffn, elem, false, d->max_seg, "FLOWSPEC_NT_DOWN", w4);
         p.down.N = d->d_model;
-        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) g->wp = (void*)take(g->bytes());
+        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) {
+            g->wp = (void*)take(g->bytes());
+            g->sp = (void*)take(g->scale_bytes());
+        }
         p.qkv.bias = (float*)take((size_t)p.qkv.n_groups * p.qkv.NT * 16 * sizeof(float));
     }
     if (d->vocab > 0) {
-        plan_gemm(L.head, (d->vocab + 15) / 16, d->d_model, elem, false, d->max_seg, "FLOWSPEC_NT_HEAD");
+        plan_gemm(L.head, (d->vocab + 15) / 16, d->d_model, elem, false, d->max_seg, "FLOWSPEC_NT_HEAD", w4);
         L.head.N = d->vocab;
         L.head.wp = (void*)take(L.head.bytes());
+        L.head.sp = (void*)take(L.head.scale_bytes());
     }
     const size_t M = align_up((size_t)d->max_seg, 16);  // fragment-major buffers hold whole 16-row tiles
     const int G = d->n_q_heads / d->n_kv_heads;
@@ -148,6 +178,12 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.off_pml = take((size_t)kMaxSplits * d->n_kv_heads * Rpad * 2 * sizeof(float));
     L.off_amw = take(M * FS_ARGMAX_CHUNKS * 2 * sizeof(int32_t));
     L.off_invf = take((size_t)(hd / 2) * sizeof(double));
+    L.off_gain = take(w4 ? (size_t)(2 * d->n_layers + 1) * d->d_model * 2 : 0);  // 4-bit: bf16 copies of the RMSNorm gains
+    // 4-bit: two buffers of per-row partial sums of squares, one entry per 16-feature tile of the residual stream
+    L.ssp_stride = (int)M;
+    const size_t ssp_bytes = w4 ? (size_t)(d->d_model / 16) * M * sizeof(float) : 0;
+    L.off_sspa = take(ssp_bytes);
+    L.off_sspb = take(ssp_bytes);
     L.total = off;
 }
 
@@ -215,17 +251,19 @@ size_t fs_stage_workspace_bytes(const fs_stage_desc* desc) {
     return L.total;
 }
 
-int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, const void* final_norm, const void* lm_head, void* workspace,
-                    size_t workspace_bytes, void* stream, fs_stage** out) {
+int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, const void* final_norm, const void* lm_head,
+                    const void* lm_head_scale, void* workspace, size_t workspace_bytes, void* stream, fs_stage** out) {
     int err;
     if (!out) return FS_EINVAL;
     *out = nullptr;
     if (!valid_desc(desc, &err)) return err;
     if (!layers) return FS_EINVAL;
-    if (desc->vocab > 0 && (!final_norm || !lm_head)) return FS_EINVAL;
+    const int w4 = desc->weight_format == FS_WFMT_INT4_G128;
+    if (desc->vocab > 0 && (!final_norm || !lm_head || (w4 && !lm_head_scale))) return FS_EINVAL;
     for (int l = 0; l < desc->n_layers; ++l) {
         const fs_layer_weights& w = layers[l];
         if (!w.rms_attn || !w.wq || !w.wk || !w.wv || !w.wo || !w.rms_ffn || !w.w_gate || !w.w_up || !w.w_down) return FS_EINVAL;
+        if (w4 && (!w.sq || !w.sk || !w.sv || !w.so || !w.s_gate || !w.s_up || !w.s_down)) return FS_EINVAL;
     }
     fs_stage* st = new (std::nothrow) fs_stage;
     if (!st) return FS_EINVAL;
@@ -239,11 +277,45 @@ int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, c
     st->ws = (unsigned char*)workspace;
     hipStream_t s = (hipStream_t)stream;
     const int hd = desc->head_dim;
+    bf16_t* gains = st->at<bf16_t>(st->L.off_gain);  // 4-bit: [2 * layer + {0: attn, 1: ffn}][d_model], final norm last
+    const size_t gain_bytes = (size_t)desc->d_model * 2;
     for (int l = 0; l < desc->n_layers; ++l) {
         LayerPlan& p = st->L.layers[l];
         const fs_layer_weights& w = layers[l];
-        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) g->wp = st->ws + (size_t)g->wp;
+        for (GemmPlan* g : {&p.qkv, &p.o, &p.gu, &p.down}) {
+            g->wp = st->ws + (size_t)g->wp;
+            g->sp = st->ws + (size_t)g->sp;
+        }
         p.qkv.bias = (float*)(st->ws + (size_t)p.qkv.bias);
+        if (w4) {
+            PackW4Args a{};
+            a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.hd = hd;
+            a.kind = PACK_QKV; a.c0 = w.wq; a.c1 = w.wk; a.c2 = w.wv; a.s0 = w.sq; a.s1 = w.sk; a.s2 = w.sv; a.dst = p.qkv.wp; a.sdst = p.qkv.sp;
+            a.N = p.qkv.N; a.K = p.qkv.K; a.NT = p.qkv.NT; a.n_groups = p.qkv.n_groups;
+            a.b0 = w.bq; a.b1 = w.bk; a.b2 = w.bv; a.bias_dst = p.qkv.bias;
+            launch_pack_w4(a, s);
+            if (!w.bq && !w.bk && !w.bv) p.qkv.bias = nullptr;
+            a = PackW4Args{};
+            a.kind = PACK_PLAIN; a.c0 = w.wo; a.s0 = w.so; a.dst = p.o.wp; a.sdst = p.o.sp; a.N = p.o.N; a.K = p.o.K; a.NT = p.o.NT;
+            a.n_groups = p.o.n_groups;
+            launch_pack_w4(a, s);
+            a = PackW4Args{};
+            a.kind = PACK_GATEUP; a.c0 = w.w_gate; a.c1 = w.w_up; a.s0 = w.s_gate; a.s1 = w.s_up; a.dst = p.gu.wp; a.sdst = p.gu.sp;
+            a.N = p.gu.N; a.K = p.gu.K; a.NT = p.gu.NT; a.n_groups = p.gu.n_groups;
+            launch_pack_w4(a, s);
+            a = PackW4Args{};
+            a.kind = PACK_PLAIN; a.c0 = w.w_down; a.s0 = w.s_down; a.dst = p.down.wp; a.sdst = p.down.sp; a.N = p.down.N; a.K = p.down.K;
+            a.NT = p.down.NT; a.n_groups = p.down.n_groups;
+            launch_pack_w4(a, s);
+            // the gains stay separate (they cannot be folded into integer codes): private bf16 copies
+            if (hipMemcpyAsync(gains + (size_t)(2 * l) * desc->d_model, w.rms_attn, gain_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+                hipMemcpyAsync(gains + (size_t)(2 * l + 1) * desc->d_model, w.rms_ffn, gain_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) {
+                g_last_hip = (int)hipGetLastError();
+                delete st;
+                return FS_EHIP;
+            }
+            continue;
+        }
         PackArgs a{};
         a.Hq = desc->n_q_heads; a.Hkv = desc->n_kv_heads; a.hd = hd;
         // QKV (attention RMSNorm gain folded in)
@@ -270,10 +342,24 @@ int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, c
     if (desc->vocab > 0) {
         GemmPlan& g = st->L.head;
         g.wp = st->ws + (size_t)g.wp;
-        PackArgs a{};
-        a.kind = PACK_PLAIN; a.src0 = lm_head; a.gain = final_norm; a.dst = g.wp; a.N = g.N; a.K = g.K; a.nkt = g.nkt; a.NT = g.NT;
-        a.n_groups = g.n_groups;
-        launch_pack(desc->dtype, a, s);
+        g.sp = st->ws + (size_t)g.sp;
+        if (w4) {
+            PackW4Args a{};
+            a.kind = PACK_PLAIN; a.c0 = lm_head; a.s0 = lm_head_scale; a.dst = g.wp; a.sdst = g.sp; a.N = g.N; a.K = g.K; a.NT = g.NT;
+            a.n_groups = g.n_groups;
+            launch_pack_w4(a, s);
+            if (hipMemcpyAsync(gains + (size_t)(2 * desc->n_layers) * desc->d_model, final_norm, gain_bytes, hipMemcpyDeviceToDevice, s) !=
+                hipSuccess) {
+                g_last_hip = (int)hipGetLastError();
+                delete st;
+                return FS_EHIP;
+            }
+        } else {
+            PackArgs a{};
+            a.kind = PACK_PLAIN; a.src0 = lm_head; a.gain = final_norm; a.dst = g.wp; a.N = g.N; a.K = g.K; a.nkt = g.nkt; a.NT = g.NT;
+            a.n_groups = g.n_groups;
+            launch_pack(desc->dtype, a, s);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = launch_rope_freq(st->at<double>(st->L.off_invf), hd, desc->rope_theta, s);
@@ -333,6 +419,15 @@ int fs_stage_profile_end(fs_stage* st, void* stream, double* total_ms, long long
     return FS_OK;
 }
 
+// dense or 4-bit projection launch, by the stage's weight format
+static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s) {
+    if (p.w4) {
+        g.Sp = p.sp;
+        return launch_gemm_w4(epi, p.NT, p.NW, p.n_groups, g, s);
+    }
+    return launch_gemm(st->d.dtype, epi, p.NT, p.NW, p.n_groups, g, s);
+}
+
 int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const void* hidden_in, int seg_off, int l_s, const int32_t* parent,
                          void* hidden_out, void* stream) {
     if (!st || l_s < 0 || seg_off < 0 || l_glo < 0) return FS_EINVAL;
@@ -361,6 +456,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     void* act = st->at<void>(L.off_act);
     uint64_t* anc = st->at<uint64_t>(L.off_anc);
     float2* rope = st->at<float2>(L.off_rope);
+    const bf16_t* gains = st->at<bf16_t>(L.off_gain);
 
     HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, st->at<double>(L.off_invf), anc, rope, s));
 
@@ -374,17 +470,27 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     int aMTW, aRB;
     attn_plan(st->elem, hd, l_s, G, d.n_kv_heads, at.L, kMaxSplits, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
 
+    // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
+    // travel beside them as partial sums (see GemmArgs::gain_next)
+    const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
+    float* sspa = st->at<float>(L.off_sspa);
+    float* sspb = st->at<float>(L.off_sspb);
+    const int res_tiles = d.d_model / 16;
+    int ssp_n_first = 0;
+    if (w4) HIP_TRY_K(st, FS_K_PREPARE, s, launch_w4_prenorm(hidden_in, d.d_model, l_s, d.d_model, gains, hb, sspa, L.ssp_stride, &ssp_n_first, s));
+
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerPlan& p = L.layers[l];
         unsigned char* klayer = (unsigned char*)kv.base + (size_t)l * kv.stride_layer * st->elem;
         const bool first = (l == 0), last = (l == d.n_layers - 1);
         // RMSNorm + QKV + RoPE + cache append
         GemmArgs g{};
-        g.X = first ? hidden_in : hb; g.x_frag = first ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
+        g.X = (first && !w4) ? hidden_in : hb; g.x_frag = (first && !w4) ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
         g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
         g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
         g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
-        HIP_TRY_K(st, FS_K_QKV, s, launch_gemm(d.dtype, EPI_QKV, p.qkv.NT, p.qkv.NW, p.qkv.n_groups, g, s));
+        g.ssp_in = sspa; g.ssp_n = first ? ssp_n_first : res_tiles; g.ssp_stride = L.ssp_stride;
+        HIP_TRY_K(st, FS_K_QKV, s, launch_proj(st, EPI_QKV, p.qkv, g, s));
         // tree attention
         at.k_layer = klayer;
         HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aMTW, aRB, s));
@@ -392,17 +498,24 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         g = GemmArgs{};
         g.X = o; g.x_frag = 1; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
         g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb; g.hb_frag = 1;
-        HIP_TRY_K(st, FS_K_OPROJ, s, launch_gemm(d.dtype, EPI_RESID, p.o.NT, p.o.NW, p.o.n_groups, g, s));
+        if (w4) {
+            g.gain_next = gains + (size_t)(2 * l + 1) * d.d_model; g.ssp_out = sspb; g.ssp_stride = L.ssp_stride;
+        }
+        HIP_TRY_K(st, FS_K_OPROJ, s, launch_proj(st, EPI_RESID, p.o, g, s));
         // RMSNorm + gate/up + SiLU * up
         g = GemmArgs{};
         g.X = hb; g.x_frag = 1; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
-        HIP_TRY_K(st, FS_K_GATEUP, s, launch_gemm(d.dtype, EPI_SWIGLU, p.gu.NT, p.gu.NW, p.gu.n_groups, g, s));
+        g.ssp_in = sspb; g.ssp_n = res_tiles; g.ssp_stride = L.ssp_stride;
+        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s));
         // down projection + residual
         g = GemmArgs{};
         g.X = act; g.x_frag = 1; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
         g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb; g.hb_frag = last ? 0 : 1;
-        HIP_TRY_K(st, FS_K_DOWN, s, launch_gemm(d.dtype, EPI_RESID, p.down.NT, p.down.NW, p.down.n_groups, g, s));
+        if (w4 && !last) {
+            g.gain_next = gains + (size_t)(2 * l + 2) * d.d_model; g.ssp_out = sspa; g.ssp_stride = L.ssp_stride;
+        }
+        HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s));
     }
     return FS_OK;
 }
@@ -417,7 +530,14 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     const GemmPlan& p = st->L.head;
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
-    HIP_TRY_K(st, FS_K_HEAD, s, launch_gemm(st->d.dtype, EPI_LOGITS, p.NT, p.NW, p.n_groups, g, s));
+    if (p.w4) {  // gained copy of the rows + their sums of squares, as at the entry of a 4-bit stage
+        void* hb = st->at<void>(st->L.off_hb);
+        float* ssp = st->at<float>(st->L.off_sspa);
+        const bf16_t* gain = st->at<bf16_t>(st->L.off_gain) + (size_t)(2 * st->d.n_layers) * st->d.d_model;
+        HIP_TRY_K(st, FS_K_PREPARE, s, launch_w4_prenorm(hidden, st->d.d_model, l_s, st->d.d_model, gain, hb, ssp, st->L.ssp_stride, &g.ssp_n, s));
+        g.X = hb; g.x_frag = 1; g.ssp_in = ssp; g.ssp_stride = st->L.ssp_stride;
+    }
+    HIP_TRY_K(st, FS_K_HEAD, s, launch_proj(st, EPI_LOGITS, p, g, s));
     HIP_TRY_K(st, FS_K_ARGMAX, s, launch_argmax(logits, l_s, st->d.vocab, FS_ARGMAX_CHUNKS, st->at<int32_t>(st->L.off_amw), amax, s));
     return FS_OK;
 }

@@ -23,6 +23,141 @@ static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p)
     return __builtin_nontemporal_load((const frag_t*)p);
 }
 
+// Cross-wave reduction through LDS and the fused epilogue, shared by the dense and the 4-bit kernels.
+template <typename T, int MT, int NT, int EPI>
+static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4 (&acc)[MT][NT], float (&ss)[MT], unsigned char* smem,
+                                                        int lane, int w, int NW, int grp, int row0) {
+    using E = Elem<T>;
+    constexpr bool NORM = (EPI != EPI_RESID);
+    const int r16 = lane & 15, g = lane >> 4;
+    // ---- cross-wave reduction through LDS ---------------------------------------------------------
+    float* red = (float*)smem;                       // [NW][MT*NT][4][64]
+    float* ssr = red + (size_t)NW * MT * NT * 256;   // [NW][MT][16]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(((size_t)w * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane] = acc[mt][nt][v];
+        if (NORM) {
+            float t = wave_xor_add(wave_xor_add(ss[mt], 16), 32);
+            if (lane < 16) ssr[(w * MT + mt) * 16 + lane] = t;
+        }
+    }
+    __syncthreads();
+
+    // ---- epilogue: an "item" is one 16x16 tile (RESID, LOGITS) or a pair of tiles (QKV, SWIGLU) ---
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    constexpr int TPI = PAIR ? 2 : 1;  // tiles per item
+    constexpr int ITEMS = MT * NT / TPI;
+    static_assert(!PAIR || NT % 2 == 0, "paired epilogues need an even NT");
+    for (int item = w; item < ITEMS; item += NW) {
+        const int mt = item / (NT / TPI), ntp = item % (NT / TPI);
+        const int m = row0 + mt * 16 + r16;
+        float y[TPI][4];
+#pragma unroll
+        for (int t = 0; t < TPI; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float s = 0.f;
+                for (int ww = 0; ww < NW; ++ww) s += red[(((size_t)ww * MT * NT + mt * NT + ntp * TPI + t) * 4 + v) * 64 + lane];
+                y[t][v] = s;
+            }
+        float rs = 1.f;
+        if (NORM) {
+            float s = 0.f;
+            for (int ww = 0; ww < NW; ++ww) s += ssr[(ww * MT + mt) * 16 + r16];
+            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
+        }
+        if constexpr (EPI != EPI_RESID) {
+            if (m >= a.M) continue;
+        }
+        const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
+        if constexpr (EPI == EPI_RESID) {
+            const int n = ptile * 16 + g * 4;
+            float hsq = 0.f;
+            if (m < a.M && n < a.N) {
+                float r[4];
+                if (a.resid_is_T) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
+                } else {
+                    f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) r[v] = rv[v];
+                }
+                f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
+                *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
+                hsq = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+                if (a.gain_next) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) h[v] *= E::to_f(((const T*)a.gain_next)[n + v]);
+                }
+                const size_t hi = a.hb_frag ? frag_major_index<T>(m, n, a.N / E::KT) : (size_t)m * a.N + n;
+                *(typename E::out4_t*)((T*)a.hb_out + hi) = E::pack4(h[0], h[1], h[2], h[3]);
+            }
+            if (a.ssp_out) {  // uniform over the workgroup; every lane of the wave is here
+                hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
+                if (g == 0 && ptile * 16 < a.N && m < a.ssp_stride) a.ssp_out[(size_t)ptile * a.ssp_stride + m] = hsq;
+            }
+        } else if constexpr (EPI == EPI_LOGITS) {
+            const int n = ptile * 16 + g * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            const int f = (ptile >> 1) * 16 + g * 4;
+            if (f < a.F) {
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float gt = rs * y[0][v], up = rs * y[1][v];
+                    o[v] = gt / (1.0f + expf(-gt)) * up;
+                }
+                *(typename E::out4_t*)((T*)a.act_out + frag_major_index<T>(m, f, a.F / E::KT)) = E::pack4(o[0], o[1], o[2], o[3]);
+            }
+        } else {  // EPI_QKV
+            const int tph = a.hd >> 4;  // tiles per head
+            const int head = ptile / tph, tih = ptile % tph;
+            float lo[4], hi[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                lo[v] = rs * y[0][v];
+                hi[v] = rs * y[1][v];
+                if (a.bias) {
+                    lo[v] += a.bias[ptile * 16 + g * 4 + v];
+                    hi[v] += a.bias[(ptile + 1) * 16 + g * 4 + v];
+                }
+            }
+            if (head < a.Hq + a.Hkv) {
+                // q / k head: the pair holds features t and t + hd/2, t = (tih/2)*16 + g*4 + v
+                const int t = (tih >> 1) * 16 + g * 4, half = a.hd >> 1;
+                const float2* cs = a.rope + (size_t)m * half + t;
+                float olo[4], ohi[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float2 c = cs[v];
+                    olo[v] = lo[v] * c.x - hi[v] * c.y;
+                    ohi[v] = hi[v] * c.x + lo[v] * c.y;
+                }
+                T* dst;
+                if (head < a.Hq)
+                    dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
+                else
+                    dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+                *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
+                *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
+            } else if (head < a.Hq + 2 * a.Hkv) {
+                // v head: natural tile order, no rotation
+                T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+                const int t = tih * 16 + g * 4;
+                *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
+                *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);
+            }
+        }
+    }
+}
+
 template <typename T, int MT, int NT, int EPI>
 __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     using E = Elem<T>;
@@ -98,120 +233,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
 
-    // ---- cross-wave reduction through LDS ---------------------------------------------------------
-    float* red = (float*)smem;                       // [NW][MT*NT][4][64]
-    float* ssr = red + (size_t)NW * MT * NT * 256;   // [NW][MT][16]
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) red[(((size_t)w * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane] = acc[mt][nt][v];
-        if (NORM) {
-            float t = wave_xor_add(wave_xor_add(ss[mt], 16), 32);
-            if (lane < 16) ssr[(w * MT + mt) * 16 + lane] = t;
-        }
-    }
-    __syncthreads();
-
-    // ---- epilogue: an "item" is one 16x16 tile (RESID, LOGITS) or a pair of tiles (QKV, SWIGLU) ---
-    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
-    constexpr int TPI = PAIR ? 2 : 1;  // tiles per item
-    constexpr int ITEMS = MT * NT / TPI;
-    static_assert(!PAIR || NT % 2 == 0, "paired epilogues need an even NT");
-    for (int item = w; item < ITEMS; item += NW) {
-        const int mt = item / (NT / TPI), ntp = item % (NT / TPI);
-        const int m = row0 + mt * 16 + r16;
-        float y[TPI][4];
-#pragma unroll
-        for (int t = 0; t < TPI; ++t)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float s = 0.f;
-                for (int ww = 0; ww < NW; ++ww) s += red[(((size_t)ww * MT * NT + mt * NT + ntp * TPI + t) * 4 + v) * 64 + lane];
-                y[t][v] = s;
-            }
-        float rs = 1.f;
-        if (NORM) {
-            float s = 0.f;
-            for (int ww = 0; ww < NW; ++ww) s += ssr[(ww * MT + mt) * 16 + r16];
-            rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
-        }
-        if (m >= a.M) continue;
-        const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
-        if constexpr (EPI == EPI_RESID) {
-            const int n = ptile * 16 + g * 4;
-            if (n < a.N) {
-                float r[4];
-                if (a.resid_is_T) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
-                } else {
-                    f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) r[v] = rv[v];
-                }
-                f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
-                *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
-                const size_t hi = a.hb_frag ? frag_major_index<T>(m, n, a.N / E::KT) : (size_t)m * a.N + n;
-                *(typename E::out4_t*)((T*)a.hb_out + hi) = E::pack4(h[0], h[1], h[2], h[3]);
-            }
-        } else if constexpr (EPI == EPI_LOGITS) {
-            const int n = ptile * 16 + g * 4;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            const int f = (ptile >> 1) * 16 + g * 4;
-            if (f < a.F) {
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float gt = rs * y[0][v], up = rs * y[1][v];
-                    o[v] = gt / (1.0f + expf(-gt)) * up;
-                }
-                *(typename E::out4_t*)((T*)a.act_out + frag_major_index<T>(m, f, a.F / E::KT)) = E::pack4(o[0], o[1], o[2], o[3]);
-            }
-        } else {  // EPI_QKV
-            const int tph = a.hd >> 4;  // tiles per head
-            const int head = ptile / tph, tih = ptile % tph;
-            float lo[4], hi[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                lo[v] = rs * y[0][v];
-                hi[v] = rs * y[1][v];
-                if (a.bias) {
-                    lo[v] += a.bias[ptile * 16 + g * 4 + v];
-                    hi[v] += a.bias[(ptile + 1) * 16 + g * 4 + v];
-                }
-            }
-            if (head < a.Hq + a.Hkv) {
-                // q / k head: the pair holds features t and t + hd/2, t = (tih/2)*16 + g*4 + v
-                const int t = (tih >> 1) * 16 + g * 4, half = a.hd >> 1;
-                const float2* cs = a.rope + (size_t)m * half + t;
-                float olo[4], ohi[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float2 c = cs[v];
-                    olo[v] = lo[v] * c.x - hi[v] * c.y;
-                    ohi[v] = hi[v] * c.x + lo[v] * c.y;
-                }
-                T* dst;
-                if (head < a.Hq)
-                    dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
-                else
-                    dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
-                *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
-                *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
-            } else if (head < a.Hq + 2 * a.Hkv) {
-                // v head: natural tile order, no rotation
-                T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
-                const int t = tih * 16 + g * 4;
-                *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
-                *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);
-            }
-        }
-    }
+    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0);
 }
 
 template <typename T, int MT, int NT, int EPI>
@@ -248,6 +270,286 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
     FS_EPI(EPI_QKV) FS_EPI(EPI_RESID) FS_EPI(EPI_SWIGLU) FS_EPI(EPI_LOGITS)
 #undef FS_EPI
     return hipErrorInvalidValue;
+}
+
+// ---- 4-bit weights (W4A16) ------------------------------------------------------------------------
+// w[n][k] = scale[n][k/128] * (code[n][k] - 8), codes 0..15, scales bf16 per 128-column group.  The stream from HBM
+// is a quarter of the bf16 one, so the unpacking has to stay cheap:
+//   * a lane's 16 bytes hold its 8 codes for each of the 4 k-tiles of one 128-column chunk; inside a dword the
+//     nibbles are ordered so that ((d >> 4j) & 0x000F000F) | 0x43004300 is the bf16 pair (128 + code[2j], 128 +
+//     code[2j+1]) — two integer instructions per pair, no conversion;
+//   * the constant 128 + 8 is taken out by one extra MFMA per k-tile whose weight operand is the constant -136
+//     (it adds -136 * sum_k x_k to every row, exactly what the offset contributes);
+//   * the group's partial result is scaled once per chunk: acc += scale[n] * acc_chunk.
+// RMSNorm: the gain cannot be folded into integer codes; a normed projection gets activations that already carry
+// the gain, and the rows' sums of squares as partial sums left by the kernel that produced them.
+template <int MT, int NT, int EPI>
+__global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
+    using T = bf16_t;
+    using E = Elem<T>;
+    using frag_t = E::frag_t;
+    constexpr bool NORM = (EPI != EPI_RESID);
+    constexpr int PF = 2;  // 128-column chunks of loads kept in flight per wave
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, NW = blockDim.x >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int grp = blockIdx.x, mb = blockIdx.y;
+    const int row0 = mb * MT * 16;
+    const int nkc = a.nkt >> 2;                       // chunks of 4 k-tiles
+    const int nsteps = (nkc - w + NW - 1) / NW;       // >= 1: the host never launches more waves than chunks
+    const unsigned char* wbase = (const unsigned char*)a.Wp + ((size_t)grp * nkc) * (size_t)(NT * 1024) + (size_t)lane * 16;
+    const bf16_t* sbase = (const bf16_t*)a.Sp + ((size_t)grp * nkc) * (size_t)(NT * 16) + g * 4;
+    const T* xrow[MT];
+    const size_t xstep = a.x_frag ? (size_t)64 * E::EPF : (size_t)E::KT;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (a.x_frag) {
+            xrow[mt] = (const T*)a.X + (((size_t)(mb * MT + mt) * a.nkt) * 64 + lane) * E::EPF;
+        } else {
+            const int m = min(row0 + mt * 16 + r16, a.M - 1);
+            xrow[mt] = (const T*)a.X + (size_t)m * a.ldx + g * E::EPF;
+        }
+    }
+
+    f32x4 acc[MT][NT];
+    float ss[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        ss[mt] = 0.f;
+        if (NORM) {  // this lane's share of the row's partial sums of squares; the cross-wave reduction adds the shares up
+            const int m = min(row0 + mt * 16 + r16, a.M - 1);
+            for (int j = w * 4 + g; j < a.ssp_n; j += 4 * NW) ss[mt] += a.ssp_in[(size_t)j * a.ssp_stride + m];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    frag_t koff;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) koff[e] = (bf16_t)(-136.0f);
+
+    u32x4 cq[PF][NT];
+    bf16x4 sq[PF][NT];
+    frag_t xq[PF][4][MT];
+    auto issue = [&](int s, int step) {
+        const int c = w + min(step, nsteps - 1) * NW;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            cq[s][nt] = __builtin_nontemporal_load((const u32x4*)(wbase + ((size_t)c * NT + nt) * 1024));
+            sq[s][nt] = *(const bf16x4*)(sbase + ((size_t)c * NT + nt) * 16);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xq[s][q][mt] = *(const frag_t*)(xrow[mt] + (size_t)(c * 4 + q) * xstep);
+        }
+    };
+    auto consume = [&](int s, int step) {
+        const bool live = step < nsteps;
+        f32x4 accg[MT][NT], acco[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acco[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) accg[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            frag_t wf[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const unsigned d = cq[s][nt][q];
+                unsigned pr[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pr[j] = ((d >> (4 * j)) & 0x000F000Fu) | 0x43004300u;
+                wf[nt] = __builtin_bit_cast(frag_t, u32x4{pr[0], pr[1], pr[2], pr[3]});
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const frag_t av = xq[s][q][mt];
+                acco[mt] = E::mma(koff, av, acco[mt]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) accg[mt][nt] = E::mma(wf[nt], av, accg[mt][nt]);
+            }
+        }
+        if (live) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float sc = (float)sq[s][nt][v];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) acc[mt][nt][v] += sc * (accg[mt][nt][v] + acco[mt][v]);
+                }
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < PF; ++s) issue(s, s);
+    const int nrounds = (nsteps + PF - 1) / PF;
+    for (int rd = 0; rd + 1 < nrounds; ++rd) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            consume(s, rd * PF + s);
+            issue(s, (rd + 1) * PF + s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
+
+    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0);
+}
+
+template <int MT, int NT, int EPI>
+static hipError_t launch_one_w4(int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    const int mblocks = (a.M + MT * 16 - 1) / (MT * 16);
+    const size_t lds = (size_t)NW * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
+    hipLaunchKernelGGL((skinny_gemm_w4_kernel<MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_mt_nt_w4(int MT, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+#define FS_CASE(mt, nt) \
+    if (MT == mt && NT == nt) return launch_one_w4<mt, nt, EPI>(NW, n_groups, a, s);
+    if constexpr (!PAIR) {
+        FS_CASE(1, 1) FS_CASE(2, 1)
+    }
+    FS_CASE(1, 2) FS_CASE(2, 2) FS_CASE(1, 4) FS_CASE(2, 4)
+#undef FS_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    // at most 32 rows per workgroup (register budget); longer segments take a second row block, whose pass over
+    // the quarter-size weights mostly hits in L2
+    const int MT = a.M <= 16 ? 1 : 2;
+    if (NW > 8) NW = 8;
+    while (NW > 1 && (size_t)NW * MT * NT * 1024 > 60 * 1024) NW >>= 1;
+    if (epi == EPI_QKV) return launch_mt_nt_w4<EPI_QKV>(MT, NT, NW, n_groups, a, s);
+    if (epi == EPI_RESID) return launch_mt_nt_w4<EPI_RESID>(MT, NT, NW, n_groups, a, s);
+    if (epi == EPI_SWIGLU) return launch_mt_nt_w4<EPI_SWIGLU>(MT, NT, NW, n_groups, a, s);
+    if (epi == EPI_LOGITS) return launch_mt_nt_w4<EPI_LOGITS>(MT, NT, NW, n_groups, a, s);
+    return hipErrorInvalidValue;
+}
+
+// Entry of a 4-bit stage (see GemmArgs::gain_next): workgroup (row tile, 512-column slice); thread (r, g, j) converts
+// the 8-element fragment pieces of k-tiles j, j + 4, ... of its slice.
+__global__ void __launch_bounds__(256) w4_prenorm_kernel(const bf16_t* X, int ldx, int M, int K, const bf16_t* gain, bf16_t* xg, float* ssp,
+                                                         int ssp_stride) {
+    __shared__ float red[16][17];
+    const int t = threadIdx.x, r = t & 15, g = (t >> 4) & 3, j = t >> 6;
+    const int mt = blockIdx.x, slice = blockIdx.y, nkt = K >> 5;
+    const int m = mt * 16 + r, mc = min(m, M - 1);
+    float ss = 0.f;
+    const int kt_end = min(nkt, slice * 16 + 16);
+    for (int kt = slice * 16 + j; kt < kt_end; kt += 4) {
+        const int k = kt * 32 + g * 8;
+        const bf16x8 x = *(const bf16x8*)(X + (size_t)mc * ldx + k);
+        const bf16x8 gn = *(const bf16x8*)(gain + k);
+        bf16x8 y;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float f = (float)x[e];
+            ss += f * f;
+            y[e] = (bf16_t)(f * (float)gn[e]);
+        }
+        *(bf16x8*)(xg + frag_major_index<bf16_t>(m, k, nkt)) = y;
+    }
+    red[t >> 4][r] = ss;
+    __syncthreads();
+    if (t < 16) {
+        float s = 0.f;
+        for (int i = 0; i < 16; ++i) s += red[i][t];
+        if (mt * 16 + t < ssp_stride) ssp[(size_t)slice * ssp_stride + mt * 16 + t] = s;
+    }
+}
+
+hipError_t launch_w4_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
+                             hipStream_t s) {
+    const int slices = (K + 511) / 512;
+    *n_slices = slices;
+    hipLaunchKernelGGL(w4_prenorm_kernel, dim3((M + 15) / 16, slices), dim3(256), 0, s, (const bf16_t*)X, ldx, M, K, (const bf16_t*)gain,
+                       (bf16_t*)xg, ssp, ssp_stride);
+    return hipGetLastError();
+}
+
+// Source row of packed row (ptile, r) for the three matrix kinds; -1 if beyond the matrix.  `which` selects the source slot.
+static __device__ __forceinline__ long long packed_source_row(int kind, int ptile, int r, int N, int Hq, int Hkv, int hd, int* which) {
+    *which = 0;
+    if (kind == PACK_PLAIN) {
+        const long long row = (long long)ptile * 16 + r;
+        return row < N ? row : -1;
+    }
+    if (kind == PACK_GATEUP) {
+        *which = ptile & 1;
+        const long long row = (long long)(ptile >> 1) * 16 + r;
+        return row < N ? row : -1;
+    }
+    const int tph = hd >> 4, head = ptile / tph, tih = ptile % tph;
+    if (head < Hq + Hkv) {
+        const int orig = (tih >> 1) + (tih & 1) * (tph >> 1);
+        *which = head < Hq ? 0 : 1;
+        return (long long)(head < Hq ? head : head - Hq) * hd + orig * 16 + r;
+    }
+    if (head < Hq + 2 * Hkv) {
+        *which = 2;
+        return (long long)(head - Hq - Hkv) * hd + tih * 16 + r;
+    }
+    return -1;
+}
+
+__global__ void pack_w4_kernel(const PackW4Args a) {
+    const int nkc = a.K / 128;
+    const size_t total = (size_t)a.n_groups * nkc * a.NT * 64;
+    for (size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x; c < total; c += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(c & 63);
+        size_t t = c >> 6;
+        const int nt = (int)(t % a.NT);
+        t /= a.NT;
+        const int chunk = (int)(t % nkc), grp = (int)(t / nkc);
+        const int r = lane & 15, g = lane >> 4;
+        const int ptile = grp * a.NT + nt;
+        int which;
+        const long long row = packed_source_row(a.kind, ptile, r, a.N, a.Hq, a.Hkv, a.hd, &which);
+        const unsigned char* codes = (const unsigned char*)(which == 0 ? a.c0 : (which == 1 ? a.c1 : a.c2));
+        unsigned d[4];
+        for (int q = 0; q < 4; ++q) {
+            unsigned v = 0;
+            for (int e = 0; e < 8; ++e) {
+                unsigned code = 8;  // rows beyond the matrix: zero weight
+                if (row >= 0) {
+                    const int k = chunk * 128 + q * 32 + g * 8 + e;
+                    const unsigned char b = codes[(size_t)row * (a.K / 2) + (k >> 1)];
+                    code = (k & 1) ? (b >> 4) : (b & 15);
+                }
+                v |= code << (4 * ((e & 1) * 4 + (e >> 1)));
+            }
+            d[q] = v;
+        }
+        ((u32x4*)a.dst)[c] = u32x4{d[0], d[1], d[2], d[3]};
+        if (g == 0) {
+            const bf16_t* sc = (const bf16_t*)(which == 0 ? a.s0 : (which == 1 ? a.s1 : a.s2));
+            ((bf16_t*)a.sdst)[(((size_t)grp * nkc + chunk) * a.NT + nt) * 16 + r] = row >= 0 ? sc[(size_t)row * nkc + chunk] : (bf16_t)0.f;
+        }
+    }
+    if (a.kind == PACK_QKV && a.bias_dst) {
+        const int np = a.n_groups * a.NT * 16;
+        for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < np; i += gridDim.x * blockDim.x) {
+            int which;
+            const long long row = packed_source_row(PACK_QKV, i >> 4, i & 15, a.N, a.Hq, a.Hkv, a.hd, &which);
+            const bf16_t* b = (const bf16_t*)(which == 0 ? a.b0 : (which == 1 ? a.b1 : a.b2));
+            a.bias_dst[i] = (row >= 0 && b) ? (float)b[row] : 0.f;
+        }
+    }
+}
+
+void launch_pack_w4(const PackW4Args& a, hipStream_t s) {
+    const size_t total = (size_t)a.n_groups * (a.K / 128) * a.NT * 64;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 65536) blocks = 65536;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(pack_w4_kernel, dim3(blocks), dim3(256), 0, s, a);
 }
 
 // ---- one-time weight re-tiling ------------------------------------------------------------------

@@ -16,7 +16,13 @@ enum PackKind { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
 struct GemmArgs {
     const void* X;   // activations, element type T: row-major [M][ldx], or fragment-major (x_frag) with K = ldx
     int x_frag;
-    const void* Wp;  // re-tiled weights: [n_groups][nkt][NT][64 lanes][16 bytes]
+    const void* Wp;  // re-tiled weights: [n_groups][nkt][NT][64 lanes][16 bytes]; 4-bit: [n_groups][K/128][NT][64 lanes][16 bytes]
+    const void* Sp;  // 4-bit only: scales, bf16 [n_groups][K/128][NT][16 rows]
+    // 4-bit only.  The RMSNorm gain cannot be folded into integer codes, so the kernel that produces a normed
+    // projection's input multiplies it in (gain_next) and leaves per-tile sums of squares of the un-gained rows
+    // (ssp_out); the consumer adds the partial sums up (ssp_in) instead of squaring its activations.
+    const float* ssp_in;   // [ssp_n][ssp_stride]: partial sums of squares per row
+    int ssp_n, ssp_stride;
     int ldx, M, K, nkt;
     int N;           // valid output features (packed order)
     float eps;
@@ -33,6 +39,8 @@ struct GemmArgs {
     float* h_out;  // [M][N] fp32
     void* hb_out;  // [M][N] T, fragment-major if hb_frag
     int hb_frag;
+    const void* gain_next;  // [N] T or null: hb_out = h * gain_next (the next RMSNorm's gain)
+    float* ssp_out;         // [N/16][ssp_stride] or null: sum over the tile's 16 features of h^2, per row
     // EPI_SWIGLU
     void* act_out;  // [M][F] fragment-major
     int F;
@@ -55,6 +63,24 @@ struct PackArgs {
     float* bias_dst;
 };
 
+struct PackW4Args {
+    // sources: codes uint8 [N][K/2] (k even in the low nibble), scales bf16 [N][K/128]; slots as in PackArgs
+    const void *c0, *c1, *c2, *s0, *s1, *s2;
+    void* dst;      // [n_groups][K/128][NT][64][16 B]
+    void* sdst;     // bf16 [n_groups][K/128][NT][16]
+    int kind, N, K, NT, n_groups;
+    int Hq, Hkv, hd;
+    const void *b0, *b1, *b2;  // biases (bf16) for QKV
+    float* bias_dst;
+};
+
 void launch_pack(int dtype, const PackArgs& a, hipStream_t s);
+void launch_pack_w4(const PackW4Args& a, hipStream_t s);
+// Entry of a 4-bit stage: xg = bf16(X * gain) fragment-major (rows padded to 16) and partial sums of squares of X per
+// 512-column slice, ssp[slice][ssp_stride]; returns the number of slices through n_slices.
+hipError_t launch_w4_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
+                             hipStream_t s);
+// 4-bit weights, bf16 activations: w[n][k] = scale[n][k/128] * (code - 8)
+hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);
 // MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);

@@ -39,10 +39,13 @@ class FlowSpecError(RuntimeError):
 class StageDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("d_model", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
                 ("d_ffn", C.c_int), ("vocab", C.c_int), ("dtype", C.c_int), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
-                ("kv_capacity", C.c_int), ("max_tree", C.c_int), ("max_seg", C.c_int)]
+                ("kv_capacity", C.c_int), ("max_tree", C.c_int), ("max_seg", C.c_int), ("weight_format", C.c_int)]
 
 
-_W = ("rms_attn", "wq", "wk", "wv", "wo", "rms_ffn", "w_gate", "w_up", "w_down", "bq", "bk", "bv")
+_W = ("rms_attn", "wq", "wk", "wv", "wo", "rms_ffn", "w_gate", "w_up", "w_down", "bq", "bk", "bv",
+      "sq", "sk", "sv", "so", "s_gate", "s_up", "s_down")
+_W_CODES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+FS_WFMT_DENSE, FS_WFMT_INT4_G128 = 0, 1
 
 
 class LayerWeights(C.Structure):
@@ -68,7 +71,7 @@ def _load():
     vp, ci, i32p = C.c_void_p, C.c_int, C.c_void_p
     lib.fs_stage_workspace_bytes.restype = C.c_size_t
     lib.fs_stage_workspace_bytes.argtypes = [C.POINTER(StageDesc)]
-    lib.fs_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), vp, vp, vp, C.c_size_t, vp, C.POINTER(vp)]
+    lib.fs_stage_create.argtypes = [C.POINTER(StageDesc), C.POINTER(LayerWeights), vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(vp)]
     lib.fs_stage_destroy.argtypes = [vp]
     lib.fs_stage_profile_begin.argtypes = [vp, ci]
     lib.fs_stage_profile_end.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
@@ -129,16 +132,17 @@ class Stage:
     """One verification stage: owns the workspace tensor and the opaque handle."""
 
     def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype, rms_eps, rope_theta, kv_capacity,
-                 max_tree, max_seg, layers, final_norm=None, lm_head=None, device="cuda", stream=None):
+                 max_tree, max_seg, layers, final_norm=None, lm_head=None, lm_head_scale=None, weight_format=FS_WFMT_DENSE, device="cuda",
+                 stream=None):
         self.desc = StageDesc(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype, rms_eps, rope_theta, kv_capacity,
-                              max_tree, max_seg)
+                              max_tree, max_seg, weight_format)
         self.dtype = torch_dtype(dtype)
         self.device = torch.device(device)
         nbytes = _lib.fs_stage_workspace_bytes(C.byref(self.desc))
         if nbytes == 0:
             # let the library name the reason
             h = C.c_void_p()
-            _check(_lib.fs_stage_create(C.byref(self.desc), None, None, None, None, 0, None, C.byref(h)) or FS_EINVAL, "fs_stage_create")
+            _check(_lib.fs_stage_create(C.byref(self.desc), None, None, None, None, None, 0, None, C.byref(h)) or FS_EINVAL, "fs_stage_create")
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         base = self.workspace.data_ptr()
         self._ws_ptr = (base + 255) // 256 * 256
@@ -147,11 +151,12 @@ class Stage:
             for n in _W:
                 t = lw.get(n)
                 if t is not None:
-                    assert t.is_cuda and t.is_contiguous() and t.dtype == self.dtype, n
+                    want = torch.uint8 if (weight_format == FS_WFMT_INT4_G128 and n in _W_CODES) else self.dtype
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == want, n
                 setattr(arr[i], n, None if t is None else t.data_ptr())
         self._handle = C.c_void_p()
-        _check(_lib.fs_stage_create(C.byref(self.desc), arr, _dp(final_norm), _dp(lm_head), C.c_void_p(self._ws_ptr), nbytes, _stream(stream),
-                                    C.byref(self._handle)), "fs_stage_create")
+        _check(_lib.fs_stage_create(C.byref(self.desc), arr, _dp(final_norm), _dp(lm_head), _dp(lm_head_scale), C.c_void_p(self._ws_ptr), nbytes,
+                                    _stream(stream), C.byref(self._handle)), "fs_stage_create")
         self.workspace_bytes = nbytes
 
     def close(self):
@@ -256,13 +261,14 @@ def seg_prune(seg_in, off, retain, res=None, seg_out=None, l_s_out=None, stream=
     return seg_out, l_s_out
 
 
-def stage_from_config(cfg, layers, final_norm=None, lm_head=None, kv_capacity=None, max_tree=None, max_seg=None, device="cuda"):
+def stage_from_config(cfg, layers, final_norm=None, lm_head=None, kv_capacity=None, max_tree=None, max_seg=None, device="cuda",
+                      lm_head_scale=None, weight_format=FS_WFMT_DENSE):
     """Build a Stage from a synth.StageConfig-like object and device weight tensors."""
     return Stage(n_layers=cfg.n_layers, d_model=cfg.d_model, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                  d_ffn=cfg.d_ffn, vocab=(cfg.vocab if lm_head is not None else 0), dtype=FS_F32 if cfg.dtype == "f32" else FS_BF16,
                  rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, kv_capacity=kv_capacity or cfg.kv_capacity,
                  max_tree=max_tree or cfg.tree_size, max_seg=max_seg or cfg.seg_len, layers=layers, final_norm=final_norm, lm_head=lm_head,
-                 device=device)
+                 lm_head_scale=lm_head_scale, weight_format=weight_format, device=device)
 
 
 # ---- host-side tree bookkeeping (no GPU) -------------------------------------------------------------------------------

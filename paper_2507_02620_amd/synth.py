@@ -171,6 +171,40 @@ def head_weights(cfg: StageConfig, seed: int = 0):
     return fn, lm
 
 
+_W4_MATRICES = {"wq": "sq", "wk": "sk", "wv": "sv", "wo": "so", "w_gate": "s_gate", "w_up": "s_up", "w_down": "s_down"}
+W4_GROUP = 128
+
+
+def quantize_w4(w: np.ndarray):
+    """Group-wise 4-bit storage of a [out, in] matrix: per row and per 128 input columns one bf16 scale (largest
+    magnitude of the group / 7) and codes in [0, 15] (nearest multiple of the scale, shifted by 8).
+    Returns (codes uint8 [out, in/2], column k even in the low nibble; scales float32 [out, in/128], bf16-exact)."""
+    n, k = w.shape
+    assert k % W4_GROUP == 0
+    g = np.ascontiguousarray(w, dtype=np.float32).reshape(n, k // W4_GROUP, W4_GROUP)
+    scale = round_bf16(np.maximum(np.abs(g).max(axis=2), np.float32(1e-8)) / np.float32(7.0))
+    q = np.clip(np.rint(g / scale[:, :, None]), -8, 7).astype(np.int16) + 8
+    q = q.reshape(n, k // 2, 2).astype(np.uint8)
+    return np.ascontiguousarray(q[:, :, 0] | (q[:, :, 1] << 4)), scale
+
+
+def layer_weights_w4(cfg: StageConfig, layer: int, seed: int = 0) -> dict:
+    """layer_weights with the seven matrices in 4-bit group storage: codes under the matrix's name, scales under s*."""
+    out = layer_weights(cfg, layer, seed)
+    for name, sname in _W4_MATRICES.items():
+        out[name], out[sname] = quantize_w4(out[name])
+    return out
+
+
+def head_weights_w4(cfg: StageConfig, seed: int = 0):
+    """(final_norm, lm_head codes, lm_head scales)."""
+    fn, lm = head_weights(cfg, seed)
+    if lm is None:
+        return None, None, None
+    codes, scales = quantize_w4(lm)
+    return fn, codes, scales
+
+
 def prefix_kv(cfg: StageConfig, layer: int, capacity: int | None = None, seed: int = 0) -> np.ndarray:
     """K and V of one layer, [2, H_kv, capacity, hd]; slots < l_glo are N(0,1) (K taken as already rotated)."""
     cap = cfg.kv_capacity if capacity is None else capacity

@@ -14,18 +14,30 @@ def to_dev(a, dtype):
 class Pair:
     """An oracle stage and a HIP stage built from identical inputs."""
 
-    def __init__(self, cfg, seed=0, head=False, capacity=None, max_tree=None, max_seg=None, oracle_layers=None):
+    def __init__(self, cfg, seed=0, head=False, capacity=None, max_tree=None, max_seg=None, oracle_layers=None, w4=False):
         self.cfg = cfg
         self.seed = seed
         self.tdtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
         cap = capacity or cfg.kv_capacity
-        layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
-        fn, lm = synth.head_weights(cfg, seed) if head else (None, None)
         nl_o = cfg.n_layers if oracle_layers is None else oracle_layers
-        self.orc = oracle.Stage(cfg.with_(n_layers=nl_o), layers[:nl_o], fn, lm, cap)
-        dev_layers = [{k: to_dev(v, self.tdtype) for k, v in lw.items()} for lw in layers]
-        self.dev_fn, self.dev_lm = to_dev(fn, self.tdtype), to_dev(lm, self.tdtype)
-        self.gpu = fs.stage_from_config(cfg, dev_layers, self.dev_fn, self.dev_lm, kv_capacity=cap, max_tree=max_tree, max_seg=max_seg)
+        lm_s = None
+        if w4:
+            # 4-bit group storage: the HIP stage gets codes and scales, the oracle the plain matrices they stand for
+            layers = [synth.layer_weights_w4(cfg, l, seed) for l in range(cfg.n_layers)]
+            fn, lm, lm_s = synth.head_weights_w4(cfg, seed) if head else (None, None, None)
+            self.orc = oracle.Stage(cfg.with_(n_layers=nl_o), [oracle.dequant_layer(lw) for lw in layers[:nl_o]], fn,
+                                    None if lm is None else oracle.dequant_w4(lm, lm_s), cap)
+            dev_layers = [{k: to_dev(v, torch.uint8 if k in oracle.W4_SCALES else self.tdtype) for k, v in lw.items()} for lw in layers]
+            self.dev_lm = to_dev(lm, torch.uint8)
+        else:
+            layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
+            fn, lm = synth.head_weights(cfg, seed) if head else (None, None)
+            self.orc = oracle.Stage(cfg.with_(n_layers=nl_o), layers[:nl_o], fn, lm, cap)
+            dev_layers = [{k: to_dev(v, self.tdtype) for k, v in lw.items()} for lw in layers]
+            self.dev_lm = to_dev(lm, self.tdtype)
+        self.dev_fn, self.dev_lm_s = to_dev(fn, self.tdtype), to_dev(lm_s, self.tdtype)
+        self.gpu = fs.stage_from_config(cfg, dev_layers, self.dev_fn, self.dev_lm, kv_capacity=cap, max_tree=max_tree, max_seg=max_seg,
+                                        lm_head_scale=self.dev_lm_s, weight_format=fs.FS_WFMT_INT4_G128 if w4 else fs.FS_WFMT_DENSE)
         torch.cuda.synchronize()
         del dev_layers  # the stage keeps its own re-tiled copy
         self.kv = self.gpu.new_kv_cache()

@@ -31,13 +31,13 @@ def test_header_constants_match_binding():
                  "FS_ARGMAX_CHUNKS"):
         m = re.search(r"#define\s+%s\s+\(?(-?\d+)\)?" % name, hdr)
         assert m and int(m.group(1)) == getattr(fs, name), name
-    assert C.sizeof(fs.AcceptResult) == 24 and C.sizeof(fs.StageDesc) == 13 * 4
+    assert C.sizeof(fs.AcceptResult) == 24 and C.sizeof(fs.StageDesc) == 14 * 4
 
 
 def test_descriptor_validation_without_gpu():
     fs = _fs()
     good = dict(n_layers=8, d_model=4096, n_q_heads=32, n_kv_heads=32, head_dim=128, d_ffn=11008, vocab=0, dtype=fs.FS_BF16, rms_eps=1e-5,
-                rope_theta=1e4, kv_capacity=2048, max_tree=64, max_seg=16)
+                rope_theta=1e4, kv_capacity=2048, max_tree=64, max_seg=16, weight_format=0)
 
     def ws(**kw):
         d = fs.StageDesc(**{**good, **kw})
@@ -51,12 +51,16 @@ def test_descriptor_validation_without_gpu():
     def create(**kw):
         d = fs.StageDesc(**{**good, **kw})
         h = C.c_void_p()
-        return fs.lib().fs_stage_create(C.byref(d), None, None, None, None, 0, None, C.byref(h))
+        return fs.lib().fs_stage_create(C.byref(d), None, None, None, None, None, 0, None, C.byref(h))
 
     assert create(dtype=7) == fs.FS_EDTYPE
     assert create(max_tree=4096) == fs.FS_ECAP
     assert create(head_dim=96) == fs.FS_EINVAL
     assert create() == fs.FS_EINVAL                    # no weights given
+    assert create(weight_format=1, dtype=fs.FS_F32) == fs.FS_EDTYPE      # 4-bit weights need bf16 activations
+    assert create(weight_format=1, d_ffn=11008 + 32) == fs.FS_EINVAL     # ... and 128-column groups
+    n4 = ws(weight_format=1)
+    assert weights / 4 <= n4 < weights / 4 * 1.2       # codes are a quarter of the bf16 bytes, plus scales and scratch
 
 
 def test_entry_points_reject_bad_arguments_before_any_gpu_work():
