@@ -172,6 +172,20 @@ def main():
     kv_bytes = cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * elem * sum(cfg.l_glo + o + n for o, n in segs)
     step_bytes = int(len(segs) * (stage_weight_bytes + head_bytes) + kv_bytes)
 
+    # the metric's two companions: MFMA utilisation of the projections and HBM rate of the tree attention
+    gemm_flops = 2.0 * sum(n for _, n in segs) * cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model
+                                                                   + 2 * cfg.n_kv_heads * cfg.head_dim * cfg.d_model + 3 * cfg.d_ffn * cfg.d_model)
+    gemm_ms = sum(prof[k][0] for k in ("qkv", "oproj", "gateup", "down")) / args.steps
+    mfma_peak = 157.3 if cfg.dtype == "f32" else 2500.0          # TFLOP/s, dense
+    at_ms, at_n = prof["attn"]
+    attn = None
+    if at_n:
+        at_bytes = kv_bytes / max(len(segs) * cfg.n_layers, 1)   # K and V of the visible slots, one layer, average segment
+        at_avg = at_ms / at_n                                     # one record spans the attention kernel and its split merge
+        attn = {"kernel": "tree_attn_kernel + attn_merge_kernel", "bound": "hbm", "algorithmic_bytes": int(at_bytes),
+                "avg_us": round(at_avg * 1e3, 2), "achieved": round(at_bytes / (at_avg * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(at_bytes / (at_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
         "value": round(tok_s, 1),
@@ -191,6 +205,11 @@ def main():
                      "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))},
         "whole_step": {"algorithmic_bytes": step_bytes, "achieved_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "tree_attention": attn,
+        "gemm_mfma": {"flops_per_step": gemm_flops, "ms_per_step": round(gemm_ms, 4),
+                      "achieved": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms else None, "peak": mfma_peak, "unit": "TFLOP/s",
+                      "util": round(gemm_flops / (gemm_ms * 1e-3) / 1e12 / mfma_peak, 5) if gemm_ms else None,
+                      "note": "rows per launch = segment length: the projections are weight-stream bound, see roofline"},
         "kernels": kern,
         "accept": {"n_acc": out_res.n_acc, "continuous": out_res.continuous, "n_retain": out_res.n_retain},
         "setup_s": round(setup_s, 1),
