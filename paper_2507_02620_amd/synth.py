@@ -63,6 +63,10 @@ CONFIGS = {
     "C3": StageConfig("C3-llama2-13b-bf16", "bf16", 10, 5120, 40, 40, 128, 13824, 32000, 2048, 96, 24, 8, 4),
     "C4": StageConfig("C4-qwen2-7b-gqa-bf16", "bf16", 7, 3584, 28, 4, 128, 18944, 152064, 4096, 128, 32, 10, 0,
                       qkv_bias=True, rms_eps=1e-6, rope_theta=1e6),
+    # chunked prefill through the same stage (Sec. III-A: the prompt is pushed through the pipeline before drafting starts):
+    # a chain of 512 / 1024 rows behind a 1024-token prefix, one segment
+    "P1": StageConfig("P1-prefill-chunk512-7b-bf16", "bf16", 8, 4096, 32, 32, 128, 11008, 0, 1024, 512, 512, 512, 1),
+    "P2": StageConfig("P2-prefill-chunk1024-7b-bf16", "bf16", 8, 4096, 32, 32, 128, 11008, 0, 1024, 1024, 1024, 1024, 1),
     "C5": StageConfig("C5-longctx-bf16", "bf16", 8, 4096, 32, 32, 128, 11008, 32000, 16384, 256, 64, 12, 4),
 }
 

@@ -1,0 +1,45 @@
+"""Chunked-prefill shape through the verification stage (Sec. III-A: the prompt passes through the same pipeline stages):
+a chain "tree" of hundreds of rows in one segment.  Same oracle, same tolerances as the tree-shaped cases."""
+import numpy as np
+import pytest
+
+from paper_2507_02620_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _chain(n):
+    return np.arange(-1, n - 1, dtype=np.int32)
+
+
+@pytest.mark.parametrize("cfg,rows", [
+    (synth.StageConfig("pf-bf16-gqa", "bf16", 2, 512, 8, 2, 64, 1408, 0, 200, 300, 300, 300, 1, qkv_bias=True), 300),
+    (synth.StageConfig("pf-bf16-mha128", "bf16", 1, 1024, 8, 8, 128, 2816, 0, 77, 512, 512, 512, 1), 512),
+    (synth.StageConfig("pf-f32", "f32", 1, 256, 4, 4, 64, 688, 0, 50, 130, 130, 130, 1), 130),
+    (synth.StageConfig("pf-bf16-1024", "bf16", 1, 512, 4, 4, 128, 1024, 0, 0, 1024, 1024, 1024, 1), 1024),
+])
+def test_chain_segment(cfg, rows):
+    from tests.gpu_util import TOL, Pair, max_rel_err
+    print(f"[case] {cfg.name} rows={rows} l_glo={cfg.l_glo}", flush=True)
+    pair = Pair(cfg, seed=4)
+    hid = synth.hidden(cfg, rows, 0, 4)
+    o, g = pair.verify_tree(_chain(rows), hid, rows)
+    err = max_rel_err(g, o)
+    print(f"  hidden max-rel-err {err:.3e}", flush=True)
+    assert err < TOL[cfg.dtype]
+    # appended K/V of the last layer
+    l = cfg.n_layers - 1
+    kv_g = pair.kv[l][:, :, cfg.l_glo:cfg.l_glo + rows].float().cpu().numpy()
+    kv_o = pair.orc.kv[l][:, :, cfg.l_glo:cfg.l_glo + rows]
+    assert max_rel_err(kv_g, kv_o) < TOL[cfg.dtype]
+
+
+def test_chain_in_two_chunks_matches_one():
+    """A 400-row chain verified as 256 + 144 rows gives the rows of the single 400-row pass (bf16 level)."""
+    from tests.gpu_util import TOL, Pair, max_rel_err
+    cfg = synth.StageConfig("pf-split", "bf16", 2, 512, 4, 4, 128, 1408, 0, 100, 400, 256, 400, 1)
+    print(f"[case] {cfg.name}", flush=True)
+    pair = Pair(cfg, seed=6)
+    hid = synth.hidden(cfg, 400, 0, 6)
+    o, g = pair.verify_tree(_chain(400), hid, 256)
+    assert max_rel_err(g, o) < TOL["bf16"]
