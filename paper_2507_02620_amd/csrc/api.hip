@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/flowspec.h"
@@ -96,7 +97,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     std::vector<LayerPlan> layers;
     GemmPlan head;
-    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, off_gain, off_sspa, off_sspb, total;
+    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, off_gain, off_sspa, off_sspb, off_part, part_bytes, off_ancall, total;
     int ssp_stride;
 };
 
@@ -179,11 +180,23 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.off_amw = take(M * FS_ARGMAX_CHUNKS * 2 * sizeof(int32_t));
     L.off_invf = take((size_t)(hd / 2) * sizeof(double));
     L.off_gain = take(w4 ? (size_t)(2 * d->n_layers + 1) * d->d_model * 2 : 0);  // 4-bit: bf16 copies of the RMSNorm gains
-    // 4-bit: two buffers of per-row partial sums of squares, one entry per 16-feature tile of the residual stream
+    // 4-bit weights and many-row segments: two buffers of per-row partial sums of squares of the residual stream, at
+    // most one entry per 16-feature tile (+ padding entries of the last feature block)
     L.ssp_stride = (int)M;
-    const size_t ssp_bytes = w4 ? (size_t)(d->d_model / 16) * M * sizeof(float) : 0;
+    const size_t ssp_bytes = d->dtype == FS_BF16 ? (size_t)(d->d_model / 16 + 4) * M * sizeof(float) : 0;
     L.off_sspa = take(ssp_bytes);
     L.off_sspb = take(ssp_bytes);
+    // many-row segments: scratch for the K-split partial results of the two residual projections
+    L.part_bytes = 0;
+    if (d->dtype == FS_BF16 && !w4 && d->max_seg >= 128) {
+        const int ms = d->max_seg, tiles = d->d_model / 16;
+        L.part_bytes = std::max(wide_partial_bytes(ms, tiles, wide_k_splits(ms, tiles, nq / 32)),
+                                wide_partial_bytes(ms, tiles, wide_k_splits(ms, tiles, d->d_ffn / 32)));
+        // shorter segments may want more slices of fewer rows: the launcher takes what fits
+        L.part_bytes = std::max(L.part_bytes, wide_partial_bytes(128, tiles, 8));
+    }
+    L.off_part = take(L.part_bytes);
+    L.off_ancall = take((size_t)d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // masks of every node while a deep tree's are built
     L.total = off;
 }
 
@@ -420,7 +433,8 @@ int fs_stage_profile_end(fs_stage* st, void* stream, double* total_ms, long long
 }
 
 // dense or 4-bit projection launch, by the stage's weight format
-static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s) {
+static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s, bool wide = false) {
+    if (wide) return launch_gemm_wide(epi, p.NT, p.n_groups * p.NT, g, st->at<float>(st->L.off_part), st->L.part_bytes, s);
     if (p.w4) {
         g.Sp = p.sp;
         return launch_gemm_w4(epi, p.NT, p.NW, p.n_groups, g, s);
@@ -441,8 +455,14 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     int rc = valid_kv(d, kv);
     if (rc) return rc;
     if (parent[0] != -1) return FS_ETOPO;
-    for (int i = 1; i < T; ++i)
+    short depth[FS_MAX_TREE];
+    int max_depth = 0;
+    depth[0] = 0;
+    for (int i = 1; i < T; ++i) {
         if (parent[i] < -1 || parent[i] >= i) return FS_ETOPO;
+        depth[i] = parent[i] < 0 ? 0 : (short)(depth[parent[i]] + 1);
+        if (depth[i] > max_depth) max_depth = depth[i];
+    }
     IdxList pl;
     rc = fill_idx(pl, parent, T);
     if (rc) return rc;
@@ -458,7 +478,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     float2* rope = st->at<float2>(L.off_rope);
     const bf16_t* gains = st->at<bf16_t>(L.off_gain);
 
-    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, l_glo, seg_off, l_s, hd, st->at<double>(L.off_invf), anc, rope, s));
+    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, max_depth, l_glo, seg_off, l_s, hd, st->at<double>(L.off_invf), st->at<uint64_t>(L.off_ancall), anc, rope, s));
 
     AttnArgs at{};
     at.q = q; at.o = o; at.M = l_s; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
@@ -472,12 +492,18 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
 
     // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
     // travel beside them as partial sums (see GemmArgs::gain_next)
+    // Segments of 128 rows and more (chunked prefill) take the MFMA-bound projection kernel; it uses the same hand-over of
+    // fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
+    const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
+    const bool handover = w4 || wide;
     float* sspa = st->at<float>(L.off_sspa);
     float* sspb = st->at<float>(L.off_sspb);
-    const int res_tiles = d.d_model / 16;
+    const int res_parts = wide ? (d.d_model / 16 + 15) / 16 * 4 : d.d_model / 16;  // partial sums per row a residual epilogue leaves
     int ssp_n_first = 0;
-    if (w4) HIP_TRY_K(st, FS_K_PREPARE, s, launch_w4_prenorm(hidden_in, d.d_model, l_s, d.d_model, gains, hb, sspa, L.ssp_stride, &ssp_n_first, s));
+    if (handover)
+        HIP_TRY_K(st, FS_K_PREPARE, s,
+                  launch_prenorm(hidden_in, d.d_model, l_s, d.d_model, w4 ? gains : nullptr, hb, sspa, L.ssp_stride, &ssp_n_first, s));
 
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerPlan& p = L.layers[l];
@@ -485,12 +511,12 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         const bool first = (l == 0), last = (l == d.n_layers - 1);
         // RMSNorm + QKV + RoPE + cache append
         GemmArgs g{};
-        g.X = (first && !w4) ? hidden_in : hb; g.x_frag = (first && !w4) ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
+        g.X = (first && !handover) ? hidden_in : hb; g.x_frag = (first && !handover) ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
         g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
         g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
         g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
-        g.ssp_in = sspa; g.ssp_n = first ? ssp_n_first : res_tiles; g.ssp_stride = L.ssp_stride;
-        HIP_TRY_K(st, FS_K_QKV, s, launch_proj(st, EPI_QKV, p.qkv, g, s));
+        g.ssp_in = sspa; g.ssp_n = first ? ssp_n_first : res_parts; g.ssp_stride = L.ssp_stride;
+        HIP_TRY_K(st, FS_K_QKV, s, launch_proj(st, EPI_QKV, p.qkv, g, s, wide));
         // tree attention
         at.k_layer = klayer;
         HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aMTW, aRB, s));
@@ -498,24 +524,24 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         g = GemmArgs{};
         g.X = o; g.x_frag = 1; g.ldx = nq; g.M = l_s; g.K = p.o.K; g.nkt = p.o.nkt; g.N = p.o.N; g.Wp = p.o.wp;
         g.resid = first ? hidden_in : (const void*)h; g.resid_is_T = first ? 1 : 0; g.h_out = h; g.hb_out = hb; g.hb_frag = 1;
-        if (w4) {
-            g.gain_next = gains + (size_t)(2 * l + 1) * d.d_model; g.ssp_out = sspb; g.ssp_stride = L.ssp_stride;
+        if (handover) {
+            g.gain_next = w4 ? gains + (size_t)(2 * l + 1) * d.d_model : nullptr; g.ssp_out = sspb; g.ssp_stride = L.ssp_stride;
         }
-        HIP_TRY_K(st, FS_K_OPROJ, s, launch_proj(st, EPI_RESID, p.o, g, s));
+        HIP_TRY_K(st, FS_K_OPROJ, s, launch_proj(st, EPI_RESID, p.o, g, s, wide));
         // RMSNorm + gate/up + SiLU * up
         g = GemmArgs{};
         g.X = hb; g.x_frag = 1; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
-        g.ssp_in = sspb; g.ssp_n = res_tiles; g.ssp_stride = L.ssp_stride;
-        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s));
+        g.ssp_in = sspb; g.ssp_n = res_parts; g.ssp_stride = L.ssp_stride;
+        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s, wide));
         // down projection + residual
         g = GemmArgs{};
         g.X = act; g.x_frag = 1; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
         g.resid = h; g.resid_is_T = 0; g.h_out = h; g.hb_out = last ? hidden_out : hb; g.hb_frag = last ? 0 : 1;
-        if (w4 && !last) {
-            g.gain_next = gains + (size_t)(2 * l + 2) * d.d_model; g.ssp_out = sspa; g.ssp_stride = L.ssp_stride;
+        if (handover && !last) {
+            g.gain_next = w4 ? gains + (size_t)(2 * l + 2) * d.d_model : nullptr; g.ssp_out = sspa; g.ssp_stride = L.ssp_stride;
         }
-        HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s));
+        HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s, wide));
     }
     return FS_OK;
 }
@@ -534,7 +560,7 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);
         const bf16_t* gain = st->at<bf16_t>(st->L.off_gain) + (size_t)(2 * st->d.n_layers) * st->d.d_model;
-        HIP_TRY_K(st, FS_K_PREPARE, s, launch_w4_prenorm(hidden, st->d.d_model, l_s, st->d.d_model, gain, hb, ssp, st->L.ssp_stride, &g.ssp_n, s));
+        HIP_TRY_K(st, FS_K_PREPARE, s, launch_prenorm(hidden, st->d.d_model, l_s, st->d.d_model, gain, hb, ssp, st->L.ssp_stride, &g.ssp_n, s));
         g.X = hb; g.x_frag = 1; g.ssp_in = ssp; g.ssp_stride = st->L.ssp_stride;
     }
     HIP_TRY_K(st, FS_K_HEAD, s, launch_proj(st, EPI_LOGITS, p, g, s));

@@ -160,6 +160,34 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         if (tile + 1 < t1) fetch(tile + 1);  // in flight while this tile is computed
         if (!computes) continue;
 
+        // ---- visibility of the tile's slots for this lane's rows: bit b <-> slot s0 + b --------------------------
+        // (slots below l_glo are always visible; draft slot l_glo + j by bit j of the row's ancestor mask; slots
+        // beyond L never).  Tiles below l_glo need no mask; a wave none of whose rows sees any slot of the tile
+        // skips it (deep chains: the upper triangle).
+        const bool need_mask = (s0 + BS > a.l_glo);  // tile touches draft slots or the tail beyond L
+        uint64_t vm[MTW];
+        if (need_mask) {
+            const int d0 = s0 - a.l_glo, valid = a.L - s0;  // valid >= 1
+            bool any = false;
+#pragma unroll
+            for (int i = 0; i < MTW; ++i) {
+                const uint64_t* am = a.anc + (size_t)seg_r[i] * FS_ANC_WORDS;
+                uint64_t m;
+                if (d0 >= 0) {
+                    const int wd = d0 >> 6, sh = d0 & 63;
+                    m = am[wd] >> sh;
+                    if (sh && wd + 1 < FS_ANC_WORDS) m |= am[wd + 1] << (64 - sh);
+                } else {
+                    m = ((1ull << (-d0)) - 1) | (am[0] << (-d0));  // 0 < -d0 < BS <= 64
+                }
+                if (valid < 64) m &= (1ull << valid) - 1;
+                if (!rok[i]) m = 0;
+                vm[i] = m >> (g * 4);
+                any |= (m != 0);
+            }
+            if (__ballot(any) == 0) continue;  // wave-uniform; the staging above is already done
+        }
+
         // ---- S^T = K . Q^T ----
         f32x4 st[MTW][BS / 16];
 #pragma unroll
@@ -175,7 +203,6 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         }
 
         // ---- mask, online softmax ----
-        const bool need_mask = (s0 + BS > a.l_glo);  // tile touches draft slots or the tail beyond L
         frag_t pf[MTW][NPF];
 #pragma unroll
         for (int i = 0; i < MTW; ++i) {
@@ -186,20 +213,15 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
                 for (int v = 0; v < 4; ++v) {
                     float s = st[i][j][v] * a.scale_log2;
                     if (need_mask) {
-                        const int slot = s0 + j * 16 + g * 4 + v;
-                        bool vis = slot < a.l_glo;
-                        if (!vis && slot < a.L) {
-                            const int dj = slot - a.l_glo;
-                            vis = (a.anc[(size_t)seg_r[i] * FS_ANC_WORDS + (dj >> 6)] >> (dj & 63)) & 1ull;
-                        }
-                        if (!vis) s = NEG_BIG;
+                        const unsigned half = (j * 16 + v) < 32 ? (unsigned)vm[i] : (unsigned)(vm[i] >> 32);
+                        if (!(half & (1u << ((j * 16 + v) & 31)))) s = NEG_BIG;
                     }
                     st[i][j][v] = s;
                     mx = fmaxf(mx, s);
                 }
             mx = wave_xor_max(wave_xor_max(mx, 16), 32);
             const float mnew = fmaxf(mrun[i], mx);
-            const float alpha = exp2f(mrun[i] - mnew);
+            const float alpha = __builtin_amdgcn_exp2f(mrun[i] - mnew);  // arguments <= 0: the raw instruction is exact enough, underflow -> 0
             mrun[i] = mnew;
             float psum = 0.f;
             float p[BS / 16][4];
@@ -208,7 +230,7 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const float s = st[i][j][v];
-                    const float e = (s <= NEG_BIG) ? 0.f : exp2f(s - mnew);
+                    const float e = (s <= NEG_BIG) ? 0.f : __builtin_amdgcn_exp2f(s - mnew);
                     p[j][v] = e;
                     psum += e;
                 }

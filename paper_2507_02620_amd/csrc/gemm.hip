@@ -23,11 +23,102 @@ static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p)
     return __builtin_nontemporal_load((const frag_t*)p);
 }
 
+// Fused epilogue for one "item": one 16x16 result tile (RESID, LOGITS) or a pair of tiles (QKV, SWIGLU) in the
+// MFMA result layout — this lane holds features g*4 + v of row m; rs is the row's RMSNorm scale.
+// Returns this lane's share of the sum of squares of the new residual-stream values (RESID), else 0.
+template <typename T, int EPI>
+static __device__ __forceinline__ float epilogue_item(const GemmArgs& a, const float (&y)[(EPI == EPI_QKV || EPI == EPI_SWIGLU) ? 2 : 1][4],
+                                                      float rs, int m, int ptile, int g) {
+    using E = Elem<T>;
+    float hsq = 0.f;
+    if constexpr (EPI != EPI_RESID) {
+        if (m >= a.M) return 0.f;
+    }
+    if constexpr (EPI == EPI_RESID) {
+        const int n = ptile * 16 + g * 4;
+        if (m < a.M && n < a.N) {
+            float r[4];
+            if (a.resid_is_T) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
+            } else {
+                f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) r[v] = rv[v];
+            }
+            f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
+            *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
+            hsq = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
+            if (a.gain_next) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) h[v] *= E::to_f(((const T*)a.gain_next)[n + v]);
+            }
+            const size_t hi = a.hb_frag ? frag_major_index<T>(m, n, a.N / E::KT) : (size_t)m * a.N + n;
+            *(typename E::out4_t*)((T*)a.hb_out + hi) = E::pack4(h[0], h[1], h[2], h[3]);
+        }
+    } else if constexpr (EPI == EPI_LOGITS) {
+        const int n = ptile * 16 + g * 4;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        const int f = (ptile >> 1) * 16 + g * 4;
+        if (f < a.F) {
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float gt = rs * y[0][v], up = rs * y[1][v];
+                o[v] = gt / (1.0f + expf(-gt)) * up;
+            }
+            *(typename E::out4_t*)((T*)a.act_out + frag_major_index<T>(m, f, a.F / E::KT)) = E::pack4(o[0], o[1], o[2], o[3]);
+        }
+    } else {  // EPI_QKV
+        const int tph = a.hd >> 4;  // tiles per head
+        const int head = ptile / tph, tih = ptile % tph;
+        if (head >= a.Hq + 2 * a.Hkv) return 0.f;  // padding tiles of the last group
+        float lo[4], hi[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            lo[v] = rs * y[0][v];
+            hi[v] = rs * y[1][v];
+            if (a.bias) {
+                lo[v] += a.bias[ptile * 16 + g * 4 + v];
+                hi[v] += a.bias[(ptile + 1) * 16 + g * 4 + v];
+            }
+        }
+        if (head < a.Hq + a.Hkv) {
+            // q / k head: the pair holds features t and t + hd/2, t = (tih/2)*16 + g*4 + v
+            const int t = (tih >> 1) * 16 + g * 4, half = a.hd >> 1;
+            const float2* cs = a.rope + (size_t)m * half + t;
+            float olo[4], ohi[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float2 c = cs[v];
+                olo[v] = lo[v] * c.x - hi[v] * c.y;
+                ohi[v] = hi[v] * c.x + lo[v] * c.y;
+            }
+            T* dst;
+            if (head < a.Hq)
+                dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
+            else
+                dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+            *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
+            *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
+        } else if (head < a.Hq + 2 * a.Hkv) {
+            // v head: natural tile order, no rotation
+            T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+            const int t = tih * 16 + g * 4;
+            *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
+            *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);
+        }
+    }
+    return hsq;
+}
+
 // Cross-wave reduction through LDS and the fused epilogue, shared by the dense and the 4-bit kernels.
 template <typename T, int MT, int NT, int EPI>
 static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4 (&acc)[MT][NT], float (&ss)[MT], unsigned char* smem,
                                                         int lane, int w, int NW, int grp, int row0) {
-    using E = Elem<T>;
     constexpr bool NORM = (EPI != EPI_RESID);
     const int r16 = lane & 15, g = lane >> 4;
     // ---- cross-wave reduction through LDS ---------------------------------------------------------
@@ -69,90 +160,12 @@ static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4
             for (int ww = 0; ww < NW; ++ww) s += ssr[(ww * MT + mt) * 16 + r16];
             rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
         }
-        if constexpr (EPI != EPI_RESID) {
-            if (m >= a.M) continue;
-        }
         const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
+        float hsq = epilogue_item<T, EPI>(a, y, rs, m, ptile, g);
         if constexpr (EPI == EPI_RESID) {
-            const int n = ptile * 16 + g * 4;
-            float hsq = 0.f;
-            if (m < a.M && n < a.N) {
-                float r[4];
-                if (a.resid_is_T) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
-                } else {
-                    f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) r[v] = rv[v];
-                }
-                f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
-                *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
-                hsq = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
-                if (a.gain_next) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) h[v] *= E::to_f(((const T*)a.gain_next)[n + v]);
-                }
-                const size_t hi = a.hb_frag ? frag_major_index<T>(m, n, a.N / E::KT) : (size_t)m * a.N + n;
-                *(typename E::out4_t*)((T*)a.hb_out + hi) = E::pack4(h[0], h[1], h[2], h[3]);
-            }
             if (a.ssp_out) {  // uniform over the workgroup; every lane of the wave is here
                 hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
                 if (g == 0 && ptile * 16 < a.N && m < a.ssp_stride) a.ssp_out[(size_t)ptile * a.ssp_stride + m] = hsq;
-            }
-        } else if constexpr (EPI == EPI_LOGITS) {
-            const int n = ptile * 16 + g * 4;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (n + v < a.N) a.logits[(size_t)m * a.N + n + v] = rs * y[0][v];
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            const int f = (ptile >> 1) * 16 + g * 4;
-            if (f < a.F) {
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float gt = rs * y[0][v], up = rs * y[1][v];
-                    o[v] = gt / (1.0f + expf(-gt)) * up;
-                }
-                *(typename E::out4_t*)((T*)a.act_out + frag_major_index<T>(m, f, a.F / E::KT)) = E::pack4(o[0], o[1], o[2], o[3]);
-            }
-        } else {  // EPI_QKV
-            const int tph = a.hd >> 4;  // tiles per head
-            const int head = ptile / tph, tih = ptile % tph;
-            float lo[4], hi[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                lo[v] = rs * y[0][v];
-                hi[v] = rs * y[1][v];
-                if (a.bias) {
-                    lo[v] += a.bias[ptile * 16 + g * 4 + v];
-                    hi[v] += a.bias[(ptile + 1) * 16 + g * 4 + v];
-                }
-            }
-            if (head < a.Hq + a.Hkv) {
-                // q / k head: the pair holds features t and t + hd/2, t = (tih/2)*16 + g*4 + v
-                const int t = (tih >> 1) * 16 + g * 4, half = a.hd >> 1;
-                const float2* cs = a.rope + (size_t)m * half + t;
-                float olo[4], ohi[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float2 c = cs[v];
-                    olo[v] = lo[v] * c.x - hi[v] * c.y;
-                    ohi[v] = hi[v] * c.x + lo[v] * c.y;
-                }
-                T* dst;
-                if (head < a.Hq)
-                    dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
-                else
-                    dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
-                *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
-                *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
-            } else if (head < a.Hq + 2 * a.Hkv) {
-                // v head: natural tile order, no rotation
-                T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
-                const int t = tih * 16 + g * 4;
-                *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
-                *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);
             }
         }
     }
@@ -270,6 +283,230 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
     FS_EPI(EPI_QKV) FS_EPI(EPI_RESID) FS_EPI(EPI_SWIGLU) FS_EPI(EPI_LOGITS)
 #undef FS_EPI
     return hipErrorInvalidValue;
+}
+
+// ---- many-row segments (chunked prefill): MFMA-bound projection ---------------------------------------------
+// From about 128 rows on, the projections stop being a weight stream and become a matrix product that has to keep
+// the MFMA pipes busy.  Workgroup = 4 waves, block = 128 rows x 256 features, wave w owns features [64w, 64w + 64)
+// for all 128 rows (8 x 4 accumulator tiles).
+//   * Weights are private to a wave, so they skip LDS: each wave streams its four tiles per k-tile straight from
+//     the re-tiled copy into registers, a ring of PFW k-tiles deep (the same coalesced 1 KiB fragment loads as
+//     the few-row kernel).
+//   * Activations are shared by the four waves: the block's 8 fragments per k-tile (fragment-major in memory, so a
+//     plain 8 KiB copy) go through a double-buffered LDS stage, one barrier per k-tile.
+//   Per k-tile and wave: 8 LDS fragment reads + 4 global fragment loads feed 32 MFMAs — half of the LDS and of the
+//   vector-memory bandwidth at full MFMA rate.
+//   * RMSNorm: the row scale comes from partial sums of squares left by the producer of the activations
+//     (GemmArgs::ssp_in), so the loop contains no per-element arithmetic.
+//   * Workgroups that share weights (the row blocks of one feature block) get consecutive slots on one XCD, so the
+//     weights are fetched from HBM once and hit in that XCD's L2 afterwards.
+constexpr int WIDE_BM_TILES = 8, WIDE_WN_TILES = 4, WIDE_WAVES = 4, WIDE_PFW = 4;
+
+//   * Projections too narrow to fill the chip (d_model outputs, a few row blocks) split K over `k_splits` workgroups;
+//     each writes its raw accumulator tiles (MFMA lane order, so 16 bytes per lane, contiguous per wave) to a scratch
+//     array and wide_fixup_kernel adds them up and runs the residual epilogue.
+template <int EPI, bool PARTIAL>
+__global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
+                                                           float* part) {
+    using T = bf16_t;
+    using E = Elem<T>;
+    using frag_t = E::frag_t;
+    constexpr bool NORM = (EPI != EPI_RESID);
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    constexpr int TPI = PAIR ? 2 : 1;
+    constexpr int BMT = WIDE_BM_TILES, WNT = WIDE_WN_TILES, PFW = WIDE_PFW;
+    __shared__ __align__(16) unsigned char xs[2][BMT * 1024];
+    __shared__ float rs_s[BMT * 16];
+
+    // XCD-aware placement: slot s of XCD x (workgroup id = s * 8 + x) takes feature block (s / m_blocks) * 8 + x, row block s % m_blocks
+    // (with split K the slot also runs over the K slices of a block, innermost)
+    const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const int per_col = m_blocks * k_splits;
+    const int col = (slot / per_col) * 8 + xcd, mb = (slot % per_col) / k_splits, ks = slot % k_splits;
+    if (col >= n_cols) return;
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int kt_lo = (int)((long long)a.nkt * ks / k_splits), nkt = (int)((long long)a.nkt * (ks + 1) / k_splits) - kt_lo;  // >= 1 (host)
+    const int mt0 = mb * BMT, m_tiles = (a.M + 15) >> 4;
+
+    if (NORM && t < BMT * 16) {
+        const int m = min(mt0 * 16 + t, a.M - 1);
+        float ssum = 0.f;
+        for (int j = 0; j < a.ssp_n; ++j) ssum += a.ssp_in[(size_t)j * a.ssp_stride + m];
+        rs_s[t] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
+    }
+
+    // this wave's weight tiles; tiles beyond the matrix re-read the last one (their results are never stored)
+    const int pt0 = (col * WIDE_WAVES + w) * WNT;
+    const unsigned char* wptr[WNT];
+#pragma unroll
+    for (int nt = 0; nt < WNT; ++nt) {
+        const int pc = min(pt0 + nt, n_tiles - 1);
+        wptr[nt] = (const unsigned char*)a.Wp + (((size_t)(pc / layout_nt) * a.nkt + kt_lo) * layout_nt + pc % layout_nt) * 1024 + (size_t)lane * 16;
+    }
+    const size_t wstep = (size_t)layout_nt * 1024;
+    // this thread's two 16-byte pieces of the activation stage: fragments w and w + 4 of the block's 8
+    const T* xptr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int mt = min(mt0 + w + 4 * i, m_tiles - 1);
+        xptr[i] = (const T*)a.X + (((size_t)mt * a.nkt + kt_lo) * 64 + lane) * E::EPF;
+    }
+    const size_t xstep = (size_t)64 * E::EPF;
+
+    f32x4 acc[BMT][WNT];
+#pragma unroll
+    for (int mt = 0; mt < BMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < WNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    frag_t wq[PFW][WNT], xr[2][2];
+    auto fetch_w = [&](int j, int kt) {
+        const int kc = min(kt, nkt - 1);
+#pragma unroll
+        for (int nt = 0; nt < WNT; ++nt) wq[j][nt] = load_w<T>(wptr[nt] + (size_t)kc * wstep);
+    };
+    auto load_x = [&](int j, int kt) {
+        const int kc = min(kt, nkt - 1);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) xr[j][i] = *(const frag_t*)(xptr[i] + (size_t)kc * xstep);
+    };
+    auto store_x = [&](int j, int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *(frag_t*)(xs[buf] + (size_t)(w + 4 * i) * 1024 + (size_t)lane * 16) = xr[j][i];
+    };
+
+#pragma unroll
+    for (int j = 0; j < PFW; ++j) fetch_w(j, j);
+    load_x(0, 0);
+    load_x(1, 1);
+    store_x(0, 0);
+    load_x(0, 2);
+    // k-tile kt: weights in wq[kt % PFW], activations in LDS buffer kt % 2; xr[(kt + 1) % 2] holds k-tile kt + 1 and
+    // xr[kt % 2] k-tile kt + 2 when the iteration starts
+    for (int kt0 = 0; kt0 < nkt; kt0 += PFW) {
+#pragma unroll
+        for (int j = 0; j < PFW; ++j) {
+            const int kt = kt0 + j;
+            if (kt < nkt) {  // uniform over the workgroup
+                __syncthreads();
+                const unsigned char* xb = xs[j & 1] + (size_t)lane * 16;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    frag_t bf[4];
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) bf[mt] = *(const frag_t*)(xb + (size_t)(h * 4 + mt) * 1024);
+#pragma unroll
+                    for (int nt = 0; nt < WNT; ++nt)
+#pragma unroll
+                        for (int mt = 0; mt < 4; ++mt) acc[h * 4 + mt][nt] = E::mma(wq[j][nt], bf[mt], acc[h * 4 + mt][nt]);
+                }
+                // every wave is past this k-tile's barrier, so nobody still reads the other buffer
+                store_x((j + 1) & 1, (j + 1) & 1);
+                load_x((j + 1) & 1, kt + 3);
+                fetch_w(j, kt + PFW);
+            }
+        }
+    }
+
+    if constexpr (PARTIAL) {
+        // raw tiles: part[ks][m tile][n tile][lane] (f32x4); tiles beyond the matrix are dropped
+        const int nt_all = n_cols * WIDE_WAVES * WNT;
+#pragma unroll
+        for (int mt = 0; mt < BMT; ++mt) {
+            if (mt0 + mt >= m_tiles) break;
+#pragma unroll
+            for (int nt = 0; nt < WNT; ++nt)
+                ((f32x4*)part)[(((size_t)ks * m_tiles + mt0 + mt) * nt_all + pt0 + nt) * 64 + lane] = acc[mt][nt];
+        }
+        return;
+    }
+    // ---- epilogue straight from the accumulators -------------------------------------------------------------
+#pragma unroll
+    for (int mt = 0; mt < BMT; ++mt) {
+        const int m = (mt0 + mt) * 16 + r16;
+        const float rs = NORM ? rs_s[mt * 16 + r16] : 1.f;
+        float hsq = 0.f;
+#pragma unroll
+        for (int ntp = 0; ntp < WNT / TPI; ++ntp) {
+            float y[TPI][4];
+#pragma unroll
+            for (int tt = 0; tt < TPI; ++tt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) y[tt][v] = acc[mt][ntp * TPI + tt][v];
+            hsq += epilogue_item<T, EPI>(a, y, rs, m, pt0 + ntp * TPI, g);
+        }
+        if constexpr (EPI == EPI_RESID) {
+            if (a.ssp_out) {  // one partial sum per wave (64 features) and row
+                hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
+                if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)(col * WIDE_WAVES + w) * a.ssp_stride + m] = hsq;
+            }
+        }
+    }
+}
+
+// Sum of the K slices' raw tiles + residual epilogue.  One wave per (row tile, 4 feature tiles): the same lane layout
+// as the accumulators, the same partial sums of squares as the direct epilogue.
+__global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n_cols, int k_splits, const float* part) {
+    const int lane = threadIdx.x & 63, r16 = lane & 15, g = lane >> 4;
+    const int m_tiles = (a.M + 15) >> 4, nt_all = n_cols * WIDE_WAVES * WIDE_WN_TILES, quads = nt_all / WIDE_WN_TILES;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);  // (row tile, quad of feature tiles)
+    if (unit >= m_tiles * quads) return;
+    const int mt = unit / quads, quad = unit % quads;
+    const int m = mt * 16 + r16;
+    float hsq = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < WIDE_WN_TILES; ++nt) {
+        const int ptile = quad * WIDE_WN_TILES + nt;
+        f32x4 sum{0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < k_splits; ++ks) sum += ((const f32x4*)part)[(((size_t)ks * m_tiles + mt) * nt_all + ptile) * 64 + lane];
+        const float y[1][4] = {{sum[0], sum[1], sum[2], sum[3]}};
+        hsq += epilogue_item<bf16_t, EPI_RESID>(a, y, 1.f, m, ptile, g);
+    }
+    if (a.ssp_out) {
+        hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
+        if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)quad * a.ssp_stride + m] = hsq;
+    }
+}
+
+int wide_k_splits(int M, int n_tiles, int nkt) {
+    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
+    const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
+    const int m_blocks = (M + WIDE_BM_TILES * 16 - 1) / (WIDE_BM_TILES * 16);
+    int s = 1;
+    while (s < 8 && n_cols * m_blocks * s * 2 <= 512 && nkt / (s * 2) >= 8) s *= 2;  // about two workgroups per compute unit
+    return s;
+}
+
+size_t wide_partial_bytes(int M, int n_tiles, int k_splits) {
+    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
+    const size_t nt_all = (size_t)((n_tiles + col_tiles - 1) / col_tiles) * col_tiles;
+    return (size_t)k_splits * ((M + 15) / 16) * nt_all * 1024;
+}
+
+hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
+    if (epi == EPI_LOGITS || !a.x_frag) return hipErrorInvalidValue;
+    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
+    const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
+    const int m_blocks = (a.M + WIDE_BM_TILES * 16 - 1) / (WIDE_BM_TILES * 16);
+    int ks = 1;
+    if (epi == EPI_RESID && part) {
+        ks = wide_k_splits(a.M, n_tiles, a.nkt);
+        while (ks > 1 && wide_partial_bytes(a.M, n_tiles, ks) > part_bytes) ks >>= 1;
+    }
+    const int grid = (n_cols + 7) / 8 * 8 * m_blocks * ks;
+    if (epi == EPI_QKV)
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_QKV, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+    else if (epi == EPI_SWIGLU)
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_SWIGLU, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+    else if (ks == 1)
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+    else {
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, true>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, ks, part);
+        const int units = ((a.M + 15) / 16) * n_cols * WIDE_WAVES;
+        hipLaunchKernelGGL(wide_fixup_kernel, dim3((units + 3) / 4), dim3(256), 0, s, a, n_cols, ks, part);
+    }
+    return hipGetLastError();
 }
 
 // ---- 4-bit weights (W4A16) ------------------------------------------------------------------------
@@ -433,9 +670,11 @@ hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs&
     return hipErrorInvalidValue;
 }
 
-// Entry of a 4-bit stage (see GemmArgs::gain_next): workgroup (row tile, 512-column slice); thread (r, g, j) converts
-// the 8-element fragment pieces of k-tiles j, j + 4, ... of its slice.
-__global__ void __launch_bounds__(256) w4_prenorm_kernel(const bf16_t* X, int ldx, int M, int K, const bf16_t* gain, bf16_t* xg, float* ssp,
+// Entry of a stage whose projections take fragment-major activations and the rows' sums of squares from their producer
+// (4-bit weights, many-row segments; see GemmArgs::gain_next): row-major rows -> fragment-major copy (times the gain, if
+// given) + partial sums of squares per 512-column slice.  Workgroup (row tile, slice); thread (r, g, j) converts the
+// 8-element fragment pieces of k-tiles j, j + 4, ... of its slice.
+__global__ void __launch_bounds__(256) prenorm_kernel(const bf16_t* X, int ldx, int M, int K, const bf16_t* gain, bf16_t* xg, float* ssp,
                                                          int ssp_stride) {
     __shared__ float red[16][17];
     const int t = threadIdx.x, r = t & 15, g = (t >> 4) & 3, j = t >> 6;
@@ -446,13 +685,16 @@ __global__ void __launch_bounds__(256) w4_prenorm_kernel(const bf16_t* X, int ld
     for (int kt = slice * 16 + j; kt < kt_end; kt += 4) {
         const int k = kt * 32 + g * 8;
         const bf16x8 x = *(const bf16x8*)(X + (size_t)mc * ldx + k);
-        const bf16x8 gn = *(const bf16x8*)(gain + k);
-        bf16x8 y;
+        bf16x8 y = x;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float f = (float)x[e];
             ss += f * f;
-            y[e] = (bf16_t)(f * (float)gn[e]);
+        }
+        if (gain) {
+            const bf16x8 gn = *(const bf16x8*)(gain + k);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = (bf16_t)((float)x[e] * (float)gn[e]);
         }
         *(bf16x8*)(xg + frag_major_index<bf16_t>(m, k, nkt)) = y;
     }
@@ -465,11 +707,11 @@ __global__ void __launch_bounds__(256) w4_prenorm_kernel(const bf16_t* X, int ld
     }
 }
 
-hipError_t launch_w4_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
+hipError_t launch_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
                              hipStream_t s) {
     const int slices = (K + 511) / 512;
     *n_slices = slices;
-    hipLaunchKernelGGL(w4_prenorm_kernel, dim3((M + 15) / 16, slices), dim3(256), 0, s, (const bf16_t*)X, ldx, M, K, (const bf16_t*)gain,
+    hipLaunchKernelGGL(prenorm_kernel, dim3((M + 15) / 16, slices), dim3(256), 0, s, (const bf16_t*)X, ldx, M, K, (const bf16_t*)gain,
                        (bf16_t*)xg, ssp, ssp_stride);
     return hipGetLastError();
 }

@@ -76,11 +76,18 @@ struct PackW4Args {
 
 void launch_pack(int dtype, const PackArgs& a, hipStream_t s);
 void launch_pack_w4(const PackW4Args& a, hipStream_t s);
-// Entry of a 4-bit stage: xg = bf16(X * gain) fragment-major (rows padded to 16) and partial sums of squares of X per
-// 512-column slice, ssp[slice][ssp_stride]; returns the number of slices through n_slices.
-hipError_t launch_w4_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
+// bf16 only.  xg = bf16(X * gain) (gain may be null) fragment-major, rows padded to 16, and partial sums of squares of X
+// per 512-column slice, ssp[slice][ssp_stride]; returns the number of slices through n_slices.
+hipError_t launch_prenorm(const void* X, int ldx, int M, int K, const void* gain, void* xg, float* ssp, int ssp_stride, int* n_slices,
                              hipStream_t s);
 // 4-bit weights, bf16 activations: w[n][k] = scale[n][k/128] * (code - 8)
 hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);
+// bf16, fragment-major activations, QKV / RESID / SWIGLU: the kernel for segments of 128 rows and more.  layout_nt and
+// n_tiles describe the re-tiled weights (tiles per group, 16-feature tiles in total); normed projections need ssp_in.
+// `part` (may be null) is scratch for K-split partial results of narrow residual projections: the split count is the
+// largest that fits part_bytes (see wide_partial_bytes; wide_k_splits gives the count the launcher would like).
+int wide_k_splits(int M, int n_tiles, int nkt);
+size_t wide_partial_bytes(int M, int n_tiles, int k_splits);
+hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s);
 // MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);

@@ -55,9 +55,65 @@ __global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent,
     }
 }
 
-hipError_t launch_tree_prepare(const IdxList& parent, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq, uint64_t* anc,
-                               float2* rope, hipStream_t s) {
-    hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope);
+// Deep trees (chains of hundreds of nodes: chunked prefill): walking to the root costs one dependent step per level, so
+// the masks and depths are built by pointer doubling instead — thread i owns node i; A[i] is the set of nodes from i up
+// to (excluding) J[i], D[i] the number of edges between them; each round ORs in A[J[i]] and jumps J[i] <- J[J[i]].
+// A lives in global scratch (T x 16 words).  The OR runs in place: a concurrent reader sees the old or the new word of
+// A[J[i]], and either contains the nodes from J[i] up to the old J[J[i]] and nothing but ancestors, which is all the next
+// round relies on.  J and D are updated behind a barrier.
+__global__ void __launch_bounds__(1024) tree_prepare_deep_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd,
+                                                                 const double* __restrict__ inv_freq, uint64_t* A,
+                                                                 uint64_t* __restrict__ anc, float2* __restrict__ rope) {
+    __shared__ short J[1024];
+    __shared__ int D[1024];
+    const int T = seg_off + l_s, i = threadIdx.x;
+    if (i < T) {
+        const int p = parent.v[i];
+        J[i] = (short)p;
+        D[i] = p >= 0 ? 1 : 0;
+        for (int w = 0; w < FS_ANC_WORDS; ++w) A[(size_t)i * FS_ANC_WORDS + w] = (w == (i >> 6)) ? (1ull << (i & 63)) : 0ull;
+    }
+    __syncthreads();
+    for (int span = 1; span < T; span <<= 1) {  // after the round every A[i] covers 2 * span levels (or reaches the root)
+        const int j = (i < T) ? J[i] : -1;
+        int jn = -1, dn = 0;
+        if (j >= 0) {
+            uint64_t add[FS_ANC_WORDS];  // ancestors of j are <= j: higher words stay as they are
+#pragma unroll
+            for (int w = 0; w < FS_ANC_WORDS; ++w) add[w] = (w <= (j >> 6)) ? A[(size_t)j * FS_ANC_WORDS + w] : 0ull;
+#pragma unroll
+            for (int w = 0; w < FS_ANC_WORDS; ++w)
+                if (add[w]) A[(size_t)i * FS_ANC_WORDS + w] |= add[w];
+            jn = J[j];
+            dn = D[i] + D[j];
+        }
+        __syncthreads();
+        if (j >= 0) {
+            J[i] = (short)jn;
+            D[i] = dn;
+        }
+        __syncthreads();
+    }
+    for (int e = i; e < l_s * FS_ANC_WORDS; e += blockDim.x)
+        anc[e] = A[(size_t)(seg_off + e / FS_ANC_WORDS) * FS_ANC_WORDS + e % FS_ANC_WORDS];
+    const int half = hd >> 1;
+    for (int e = i; e < l_s * half; e += blockDim.x) {
+        const int r = e / half, t = e % half;
+        const double two_pi = 6.283185307179586476925286766559;
+        double ang = (double)(l_glo + D[seg_off + r]) * inv_freq[t];
+        ang -= two_pi * floor(ang / two_pi);
+        float sn, cs;
+        sincosf((float)ang, &sn, &cs);
+        rope[e] = make_float2(cs, sn);
+    }
+}
+
+hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq,
+                               uint64_t* anc_all, uint64_t* anc, float2* rope, hipStream_t s) {
+    if (max_depth > 32)
+        hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all, anc, rope);
+    else
+        hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope);
     return hipGetLastError();
 }
 
