@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--weights", default="dense", choices=["dense", "int4"],
                     help="int4: 4-bit group weights with bf16 activations (W4A16, the paper's 13B setting); bf16 workloads only")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
+    ap.add_argument("--graph", action="store_true", help="capture one whole step into a HIP graph and time its replays")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -141,12 +142,36 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    run = step
+    if args.graph:
+        # every launch of the step (the library's kernels take the tree as kernel arguments, nothing is allocated or
+        # cleared by memset) goes into one graph on a side stream; a replay is one step
         step()
+        torch.cuda.synchronize()
+        cap_stream = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap_stream):
+            cur = torch.cuda.current_stream().cuda_stream
+            l_glo = cfg.l_glo
+            for i, (off, n) in enumerate(segs):
+                stage.tree_verify_stage(kv, l_glo, l_glo + off, hid_segs[i], off, tree.parent[: off + n], out_segs[i], stream=cur)
+                if use_head:
+                    stage.tree_logits(out_segs[i], logits[off:off + n], amax[off:off + n], stream=cur)
+            if use_head:
+                logits[plant_rows, plant_toks] += 100.0
+                fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work, stream=cur)
+            else:
+                amax[plant_rows] = plant_toks.to(torch.int32)
+                fs.tree_accept(None, amax, token_d, parent_d, T, res, retain, work, stream=cur)
+            stage.kv_compact(kv, l_glo, l_glo + T, retain, res=res, new_len=new_len, stream=cur)
+            fs.seg_prune(hid_segs[-1], segs[-1][0], retain, res=res, seg_out=pr_out, l_s_out=pr_n, stream=cur)
+        run = graph.replay
+    for _ in range(args.warmup):
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -186,6 +211,21 @@ def main():
                 "avg_us": round(at_avg * 1e3, 2), "achieved": round(at_bytes / (at_avg * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(at_bytes / (at_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # many-row segments run the MFMA-bound projection kernel: the dominant kernel is then priced against the matrix peak
+    wide = cfg.dtype == "bf16" and not w4 and cfg.seg_len >= 128
+    if wide:
+        gu_flops = 2.0 * min(cfg.seg_len, T) * 2 * cfg.d_ffn * cfg.d_model
+        gu_tf = gu_flops / (gu_avg_ms * 1e-3) / 1e12 if gu_n else 0.0
+        roofline = {"kernel": "wide_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up, %d rows)" % min(cfg.seg_len, T), "bound": "mfma",
+                    "achieved": round(gu_tf, 1), "peak": mfma_peak, "unit": "TFLOP/s", "frac": round(gu_tf / mfma_peak, 4),
+                    "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_flops": gu_flops,
+                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower()))}
+    else:
+        roofline = {"kernel": "skinny_gemm%s_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)" % ("_w4" if w4 else ""), "bound": "hbm",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
+                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))}
+
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
         "value": round(tok_s, 1),
@@ -199,17 +239,15 @@ def main():
                    "kv_prefix": cfg.l_glo, "tree_nodes": T, "segment": cfg.seg_len, "segments_per_step": len(segs),
                    "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs),
                    "acceptance": "greedy" if args.temperature <= 0 else "sampled, temperature %g" % args.temperature},
-        "roofline": {"kernel": "skinny_gemm%s_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)" % ("_w4" if w4 else ""), "bound": "hbm",
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
-                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))},
+        "roofline": roofline,
         "whole_step": {"algorithmic_bytes": step_bytes, "achieved_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "tree_attention": attn,
         "gemm_mfma": {"flops_per_step": gemm_flops, "ms_per_step": round(gemm_ms, 4),
                       "achieved": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms else None, "peak": mfma_peak, "unit": "TFLOP/s",
                       "util": round(gemm_flops / (gemm_ms * 1e-3) / 1e12 / mfma_peak, 5) if gemm_ms else None,
-                      "note": "rows per launch = segment length: the projections are weight-stream bound, see roofline"},
+                      "note": ("rows per launch = segment length: MFMA-bound projection kernel" if wide else
+                               "rows per launch = segment length: the projections are weight-stream bound, see roofline")},
         "kernels": kern,
         "accept": {"n_acc": out_res.n_acc, "continuous": out_res.continuous, "n_retain": out_res.n_retain},
         "setup_s": round(setup_s, 1),
