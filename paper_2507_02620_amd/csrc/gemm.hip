@@ -300,13 +300,13 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
 //     (GemmArgs::ssp_in), so the loop contains no per-element arithmetic.
 //   * Workgroups that share weights (the row blocks of one feature block) get consecutive slots on one XCD, so the
 //     weights are fetched from HBM once and hit in that XCD's L2 afterwards.
-constexpr int WIDE_BM_TILES = 8, WIDE_WN_TILES = 4, WIDE_WAVES = 4, WIDE_PFW = 4;
+constexpr int WIDE_WN_TILES = 4, WIDE_WAVES = 4, WIDE_PFW = 5;
 
 //   * Projections too narrow to fill the chip (d_model outputs, a few row blocks) split K over `k_splits` workgroups;
 //     each writes its raw accumulator tiles (MFMA lane order, so 16 bytes per lane, contiguous per wave) to a scratch
 //     array and wide_fixup_kernel adds them up and runs the residual epilogue.
-template <int EPI, bool PARTIAL>
-__global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
+template <int EPI, bool PARTIAL, int BMT>
+__global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
                                                            float* part) {
     using T = bf16_t;
     using E = Elem<T>;
@@ -314,7 +314,8 @@ __global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int
     constexpr bool NORM = (EPI != EPI_RESID);
     constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
     constexpr int TPI = PAIR ? 2 : 1;
-    constexpr int BMT = WIDE_BM_TILES, WNT = WIDE_WN_TILES, PFW = WIDE_PFW;
+    constexpr int WNT = WIDE_WN_TILES, PFW = BMT == 4 ? WIDE_PFW - 1 : WIDE_PFW;
+    constexpr int XL = BMT / 4;  // 16-byte pieces of the activation stage per thread
     __shared__ __align__(16) unsigned char xs[2][BMT * 1024];
     __shared__ float rs_s[BMT * 16];
 
@@ -336,23 +337,27 @@ __global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int
         rs_s[t] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
     }
 
-    // this wave's weight tiles; tiles beyond the matrix re-read the last one (their results are never stored)
+    // this wave's weight tiles; tiles beyond the matrix re-read the last one (their results are never stored).
+    // Addresses are a uniform base plus a 32-bit byte offset per lane (one matrix is far below 4 GiB), advanced by one
+    // k-tile per fetch until the last k-tile of the slice is reached.
     const int pt0 = (col * WIDE_WAVES + w) * WNT;
-    const unsigned char* wptr[WNT];
+    const unsigned char* wbase = (const unsigned char*)a.Wp;
+    const unsigned char* xbase = (const unsigned char*)a.X;
+    unsigned woff[WNT], xoff[XL];
 #pragma unroll
     for (int nt = 0; nt < WNT; ++nt) {
         const int pc = min(pt0 + nt, n_tiles - 1);
-        wptr[nt] = (const unsigned char*)a.Wp + (((size_t)(pc / layout_nt) * a.nkt + kt_lo) * layout_nt + pc % layout_nt) * 1024 + (size_t)lane * 16;
+        woff[nt] = (unsigned)((((size_t)(pc / layout_nt) * a.nkt + kt_lo) * layout_nt + pc % layout_nt) * 1024 + (size_t)lane * 16);
     }
-    const size_t wstep = (size_t)layout_nt * 1024;
-    // this thread's two 16-byte pieces of the activation stage: fragments w and w + 4 of the block's 8
-    const T* xptr[2];
+    const unsigned wstep = (unsigned)layout_nt * 1024;
+    // this thread's 16-byte pieces of the activation stage: fragments w (and w + 4) of the block's BMT
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < XL; ++i) {
         const int mt = min(mt0 + w + 4 * i, m_tiles - 1);
-        xptr[i] = (const T*)a.X + (((size_t)mt * a.nkt + kt_lo) * 64 + lane) * E::EPF;
+        xoff[i] = (unsigned)((((size_t)mt * a.nkt + kt_lo) * 64 + lane) * 16);
     }
-    const size_t xstep = (size_t)64 * E::EPF;
+    const unsigned xstep = 1024;
+    int wk = 0, xk = 0;  // k-tiles already fetched (weights / activations)
 
     f32x4 acc[BMT][WNT];
 #pragma unroll
@@ -360,39 +365,46 @@ __global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int
 #pragma unroll
         for (int nt = 0; nt < WNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    frag_t wq[PFW][WNT], xr[2][2];
-    auto fetch_w = [&](int j, int kt) {
-        const int kc = min(kt, nkt - 1);
+    frag_t wq[PFW][WNT], xr[2][XL];
+    auto fetch_w = [&](int j, int) {
 #pragma unroll
-        for (int nt = 0; nt < WNT; ++nt) wq[j][nt] = load_w<T>(wptr[nt] + (size_t)kc * wstep);
+        for (int nt = 0; nt < WNT; ++nt) wq[j][nt] = load_w<T>(wbase + woff[nt]);
+        const unsigned adv = (++wk < nkt) ? wstep : 0u;  // past the slice's end the last k-tile is re-read (and never used)
+#pragma unroll
+        for (int nt = 0; nt < WNT; ++nt) woff[nt] += adv;
     };
-    auto load_x = [&](int j, int kt) {
-        const int kc = min(kt, nkt - 1);
+    auto load_x = [&](int j, int) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) xr[j][i] = *(const frag_t*)(xptr[i] + (size_t)kc * xstep);
+        for (int i = 0; i < XL; ++i) xr[j][i] = *(const frag_t*)(xbase + xoff[i]);
+        const unsigned adv = (++xk < nkt) ? xstep : 0u;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) xoff[i] += adv;
     };
     auto store_x = [&](int j, int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) *(frag_t*)(xs[buf] + (size_t)(w + 4 * i) * 1024 + (size_t)lane * 16) = xr[j][i];
+        for (int i = 0; i < XL; ++i) *(frag_t*)(xs[buf] + (size_t)(w + 4 * i) * 1024 + (size_t)lane * 16) = xr[j][i];
     };
-
+    // Pipeline, k-tile kt: weights in wq[kt % PFW] (fetched PFW k-tiles ahead: the weight fetch is the longest latency in the
+    // loop), activations in LDS buffer kt & 1; xr[(kt + 1) & 1] holds k-tile kt + 1 and xr[kt & 1] k-tile kt + 2 when the
+    // iteration starts.  One barrier per k-tile: it publishes buffer kt & 1 (filled during k-tile kt - 1) and tells that
+    // nobody still reads the other buffer, which the refill at the end of the iteration overwrites.
 #pragma unroll
     for (int j = 0; j < PFW; ++j) fetch_w(j, j);
     load_x(0, 0);
     load_x(1, 1);
     store_x(0, 0);
     load_x(0, 2);
-    // k-tile kt: weights in wq[kt % PFW], activations in LDS buffer kt % 2; xr[(kt + 1) % 2] holds k-tile kt + 1 and
-    // xr[kt % 2] k-tile kt + 2 when the iteration starts
-    for (int kt0 = 0; kt0 < nkt; kt0 += PFW) {
+    constexpr int U = (PFW % 2 == 0) ? PFW : 2 * PFW;  // unroll so that kt % PFW and kt & 1 are compile-time
+    for (int kt0 = 0; kt0 < nkt; kt0 += U) {
 #pragma unroll
-        for (int j = 0; j < PFW; ++j) {
-            const int kt = kt0 + j;
+        for (int ju = 0; ju < U; ++ju) {
+            const int kt = kt0 + ju;
+            const int j = ju % PFW;
             if (kt < nkt) {  // uniform over the workgroup
                 __syncthreads();
-                const unsigned char* xb = xs[j & 1] + (size_t)lane * 16;
+                const unsigned char* xb = xs[ju & 1] + (size_t)lane * 16;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < BMT / 4; ++h) {
                     frag_t bf[4];
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt) bf[mt] = *(const frag_t*)(xb + (size_t)(h * 4 + mt) * 1024);
@@ -401,9 +413,8 @@ __global__ void __launch_bounds__(256, 2) wide_gemm_kernel(const GemmArgs a, int
 #pragma unroll
                         for (int mt = 0; mt < 4; ++mt) acc[h * 4 + mt][nt] = E::mma(wq[j][nt], bf[mt], acc[h * 4 + mt][nt]);
                 }
-                // every wave is past this k-tile's barrier, so nobody still reads the other buffer
-                store_x((j + 1) & 1, (j + 1) & 1);
-                load_x((j + 1) & 1, kt + 3);
+                store_x((ju + 1) & 1, (ju + 1) & 1);
+                load_x((ju + 1) & 1, kt + 3);
                 fetch_w(j, kt + PFW);
             }
         }
@@ -469,10 +480,19 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
     }
 }
 
+// Row tiles per block: 8 (128 rows: each weight fragment feeds 8 MFMAs).  Blocks of 4 row tiles double the number of
+// workgroups but halve the reuse of a weight fragment; measured slower at every shape tried (512 rows: gate/up 131 -> 169 us,
+// 1024 rows: 228 -> 318 us), so they are only reachable through FLOWSPEC_WIDE_BMT=4 (for experiments).
+int wide_bmt(int, int) {
+    static const int forced = [] { const char* v = getenv("FLOWSPEC_WIDE_BMT"); return v ? atoi(v) : 0; }();
+    return forced == 4 ? 4 : 8;
+}
+
 int wide_k_splits(int M, int n_tiles, int nkt) {
     const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
     const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
-    const int m_blocks = (M + WIDE_BM_TILES * 16 - 1) / (WIDE_BM_TILES * 16);
+    const int bm = wide_bmt(M, n_tiles) * 16;
+    const int m_blocks = (M + bm - 1) / bm;
     int s = 1;
     while (s < 8 && n_cols * m_blocks * s * 2 <= 512 && nkt / (s * 2) >= 8) s *= 2;  // about two workgroups per compute unit
     return s;
@@ -484,11 +504,11 @@ size_t wide_partial_bytes(int M, int n_tiles, int k_splits) {
     return (size_t)k_splits * ((M + 15) / 16) * nt_all * 1024;
 }
 
-hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
-    if (epi == EPI_LOGITS || !a.x_frag) return hipErrorInvalidValue;
+template <int BMT>
+static hipError_t launch_wide_bmt(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
     const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
     const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
-    const int m_blocks = (a.M + WIDE_BM_TILES * 16 - 1) / (WIDE_BM_TILES * 16);
+    const int m_blocks = (a.M + BMT * 16 - 1) / (BMT * 16);
     int ks = 1;
     if (epi == EPI_RESID && part) {
         ks = wide_k_splits(a.M, n_tiles, a.nkt);
@@ -496,17 +516,23 @@ hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs&
     }
     const int grid = (n_cols + 7) / 8 * 8 * m_blocks * ks;
     if (epi == EPI_QKV)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_QKV, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_QKV, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
     else if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_SWIGLU, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_SWIGLU, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
     else if (ks == 1)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, false>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
     else {
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, true>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, ks, part);
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, true, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, ks, part);
         const int units = ((a.M + 15) / 16) * n_cols * WIDE_WAVES;
         hipLaunchKernelGGL(wide_fixup_kernel, dim3((units + 3) / 4), dim3(256), 0, s, a, n_cols, ks, part);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
+    if (epi == EPI_LOGITS || !a.x_frag) return hipErrorInvalidValue;
+    if (wide_bmt(a.M, n_tiles) == 4) return launch_wide_bmt<4>(epi, layout_nt, n_tiles, a, part, part_bytes, s);
+    return launch_wide_bmt<8>(epi, layout_nt, n_tiles, a, part, part_bytes, s);
 }
 
 // ---- 4-bit weights (W4A16) ------------------------------------------------------------------------
