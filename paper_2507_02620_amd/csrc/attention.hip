@@ -292,6 +292,7 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
     }
 }
 
+
 // Combine the splits: one thread per (KV head, row, 4 head-dim elements).
 template <typename T>
 __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
