@@ -552,7 +552,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
     using E = Elem<T>;
     using frag_t = E::frag_t;
     constexpr bool NORM = (EPI != EPI_RESID);
-    constexpr int PF = 2;  // 128-column chunks of loads kept in flight per wave
+    constexpr int PF = 2;  // 128-column chunks of loads kept in flight per wave (4 was measured slower: qkv 14.5 -> 16.9 us at 16 rows)
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, NW = blockDim.x >> 6;
     const int r16 = lane & 15, g = lane >> 4;
