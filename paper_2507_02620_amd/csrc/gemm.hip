@@ -23,12 +23,38 @@ static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p)
     return __builtin_nontemporal_load((const frag_t*)p);
 }
 
+// Residual-stream values [m][n .. n+3] (fp32 stream, or the T-typed stage input at the first layer).
+template <typename T>
+static __device__ __forceinline__ f32x4 load_resid(const GemmArgs& a, int m, int n) {
+    using E = Elem<T>;
+    if (a.resid_is_T) {
+        const T* p = (const T*)a.resid + (size_t)m * a.N + n;
+        return f32x4{E::to_f(p[0]), E::to_f(p[1]), E::to_f(p[2]), E::to_f(p[3])};
+    }
+    return *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
+}
+
+// The residual values of the item a wave will finish first (item w), fetched before the K loop so that the epilogue does
+// not start with a dependent global load.  Only this workgroup ever writes those elements, so reading them early is safe
+// even when the projection updates the residual stream in place.
+template <typename T, int MT, int NT, int EPI>
+static __device__ __forceinline__ f32x4 prefetch_resid(const GemmArgs& a, int w, int grp, int row0, int r16, int g) {
+    f32x4 v{0.f, 0.f, 0.f, 0.f};
+    if constexpr (EPI == EPI_RESID) {
+        if (w < MT * NT) {
+            const int m = row0 + (w / NT) * 16 + r16, n = (grp * NT + w % NT) * 16 + g * 4;
+            if (m < a.M && n < a.N) v = load_resid<T>(a, m, n);
+        }
+    }
+    return v;
+}
+
 // Fused epilogue for one "item": one 16x16 result tile (RESID, LOGITS) or a pair of tiles (QKV, SWIGLU) in the
 // MFMA result layout — this lane holds features g*4 + v of row m; rs is the row's RMSNorm scale.
 // Returns this lane's share of the sum of squares of the new residual-stream values (RESID), else 0.
 template <typename T, int EPI>
 static __device__ __forceinline__ float epilogue_item(const GemmArgs& a, const float (&y)[(EPI == EPI_QKV || EPI == EPI_SWIGLU) ? 2 : 1][4],
-                                                      float rs, int m, int ptile, int g) {
+                                                      float rs, int m, int ptile, int g, const f32x4* resid_pre = nullptr) {
     using E = Elem<T>;
     float hsq = 0.f;
     if constexpr (EPI != EPI_RESID) {
@@ -37,15 +63,8 @@ static __device__ __forceinline__ float epilogue_item(const GemmArgs& a, const f
     if constexpr (EPI == EPI_RESID) {
         const int n = ptile * 16 + g * 4;
         if (m < a.M && n < a.N) {
-            float r[4];
-            if (a.resid_is_T) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) r[v] = E::to_f(((const T*)a.resid)[(size_t)m * a.N + n + v]);
-            } else {
-                f32x4 rv = *(const f32x4*)((const float*)a.resid + (size_t)m * a.N + n);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) r[v] = rv[v];
-            }
+            const f32x4 rv = resid_pre ? *resid_pre : load_resid<T>(a, m, n);
+            const float r[4] = {rv[0], rv[1], rv[2], rv[3]};
             f32x4 h{r[0] + y[0][0], r[1] + y[0][1], r[2] + y[0][2], r[3] + y[0][3]};
             *(f32x4*)(a.h_out + (size_t)m * a.N + n) = h;
             hsq = h[0] * h[0] + h[1] * h[1] + h[2] * h[2] + h[3] * h[3];
@@ -118,7 +137,7 @@ static __device__ __forceinline__ float epilogue_item(const GemmArgs& a, const f
 // Cross-wave reduction through LDS and the fused epilogue, shared by the dense and the 4-bit kernels.
 template <typename T, int MT, int NT, int EPI>
 static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4 (&acc)[MT][NT], float (&ss)[MT], unsigned char* smem,
-                                                        int lane, int w, int NW, int grp, int row0) {
+                                                        int lane, int w, int NW, int grp, int row0, const f32x4& resid_first) {
     constexpr bool NORM = (EPI != EPI_RESID);
     const int r16 = lane & 15, g = lane >> 4;
     // ---- cross-wave reduction through LDS ---------------------------------------------------------
@@ -161,7 +180,7 @@ static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4
             rs = 1.0f / sqrtf(s / (float)a.K + a.eps);
         }
         const int ptile = grp * NT + ntp * TPI;  // first packed tile of the item
-        float hsq = epilogue_item<T, EPI>(a, y, rs, m, ptile, g);
+        float hsq = epilogue_item<T, EPI>(a, y, rs, m, ptile, g, item == w ? &resid_first : nullptr);
         if constexpr (EPI == EPI_RESID) {
             if (a.ssp_out) {  // uniform over the workgroup; every lane of the wave is here
                 hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
@@ -201,6 +220,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
         }
     }
 
+    const f32x4 resid_first = prefetch_resid<T, MT, NT, EPI>(a, w, grp, row0, r16, g);
     f32x4 acc[MT][NT];
     float ss[MT];
 #pragma unroll
@@ -246,7 +266,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
 
-    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0);
+    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0, resid_first);
 }
 
 template <typename T, int MT, int NT, int EPI>
@@ -574,6 +594,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
         }
     }
 
+    const f32x4 resid_first = prefetch_resid<T, MT, NT, EPI>(a, w, grp, row0, r16, g);
     f32x4 acc[MT][NT];
     float ss[MT];
 #pragma unroll
@@ -659,7 +680,7 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
 
-    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0);
+    reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0, resid_first);
 }
 
 template <int MT, int NT, int EPI>
