@@ -43,3 +43,17 @@ def test_chain_in_two_chunks_matches_one():
     hid = synth.hidden(cfg, 400, 0, 6)
     o, g = pair.verify_tree(_chain(400), hid, 256)
     assert max_rel_err(g, o) < TOL["bf16"]
+
+
+def test_chain_at_bench_width():
+    """Workload P1's layer shape and row count (512-row chain behind a 1024-token prefix, d_model 4096, FFN 11008) through one
+    layer, in the launch configuration bench.py times: every output row against the oracle."""
+    from tests.gpu_util import TOL, Pair, max_rel_err
+    cfg = synth.CONFIGS["P1"].with_(n_layers=1)
+    print(f"[case] {cfg.name} 1 layer rows={cfg.tree_size}", flush=True)
+    pair = Pair(cfg, seed=0)
+    hid = synth.hidden(cfg, cfg.tree_size, 0, 0)
+    o, g = pair.verify_tree(_chain(cfg.tree_size), hid, cfg.seg_len)
+    err = max_rel_err(g, o)
+    print(f"  hidden max-rel-err {err:.3e}", flush=True)
+    assert err < TOL["bf16"]
