@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--weights", default="dense", choices=["dense", "int4"],
                     help="int4: 4-bit group weights with bf16 activations (W4A16, the paper's 13B setting); bf16 workloads only")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
+    ap.add_argument("--no-probes", action="store_true", help="skip the achievable-peak probes (pure streaming read, pure MFMA loop) and the "
+                    "large-size KV compaction measurement")
     ap.add_argument("--graph", action="store_true", help="capture one whole step into a HIP graph and time its replays")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
@@ -226,6 +228,48 @@ def main():
                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))}
 
+    # KV compaction of the step: rows kept in the cache that actually move (retained draft rows), read + written, K and V, all layers
+    cp_ms, cp_n = prof["compact"]
+    n_keep = max(out_res.n_retain, 0)
+    cp_bytes = 2 * 2 * n_keep * cfg.n_kv_heads * cfg.head_dim * elem * cfg.n_layers
+    kvc = {"rows_kept": n_keep, "algorithmic_bytes": cp_bytes, "avg_us": round(cp_ms / max(cp_n, 1) * 1e3, 2),
+           "achieved_GBs": round(cp_bytes / (cp_ms / max(cp_n, 1) * 1e-3) / 1e9, 1) if cp_n and cp_ms > 0 else None,
+           "note": "a few rows per step: launch-latency bound at this size; see kv_compact_large"}
+    achievable = None
+    if not args.no_probes:
+        # (1) what a launch can reach at all on this machine; (2) compaction at the largest size one call takes (1024-node
+        # tree, every other node kept): the HBM-bound regime of the same kernel
+        big = torch.empty((3 << 30) + 64, dtype=torch.uint8, device=dev)
+        achievable = {"hbm_stream_read_GBs": round(fs.probe_stream_read(big, 176 << 20, 20), 1),
+                      "hbm_stream_read_small_GBs": round(fs.probe_stream_read(big, 32 << 20, 20), 1),
+                      "mfma_bf16_TFLOPs": round(fs.probe_mfma_bf16(big, 5), 1),
+                      "note": "one-pass reads of 176 MiB / 32 MiB per launch rotating through 3 GiB; register-resident 16x16x32 bf16 MFMA loop"}
+        del big
+        torch.cuda.empty_cache()
+        Tb = 1024
+        # compaction only looks at the cache geometry, so a stage with the workload's layers / KV heads / head dim and
+        # token-sized projections stands in (no second copy of the weights)
+        cfg_b = cfg.with_(d_model=128, d_ffn=128, vocab=0, tree_size=Tb, seg_len=16)
+        lw_b = [{k: up(v) for k, v in synth.layer_weights(cfg_b, l, seed).items()} for l in range(cfg_b.n_layers)]
+        stage_b = fs.stage_from_config(cfg_b, lw_b, kv_capacity=cfg.l_glo + Tb + 64, max_tree=Tb, max_seg=16)
+        kv_b = stage_b.new_kv_cache()
+        keep = list(range(0, Tb, 2))
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        for _ in range(2):
+            stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
+        ev0.record()
+        for _ in range(reps):
+            stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms_b = ev0.elapsed_time(ev1) / reps
+        bytes_b = 2 * 2 * len(keep) * cfg.n_kv_heads * cfg.head_dim * elem * cfg.n_layers
+        kvc["kv_compact_large"] = {"rows_kept": len(keep), "of_tree_nodes": Tb, "algorithmic_bytes": bytes_b, "avg_us": round(ms_b * 1e3, 2),
+                                   "achieved_GBs": round(bytes_b / (ms_b * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                                   "frac": round(bytes_b / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del stage_b, kv_b, lw_b
+
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
         "value": round(tok_s, 1),
@@ -243,6 +287,8 @@ def main():
         "whole_step": {"algorithmic_bytes": step_bytes, "achieved_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "tree_attention": attn,
+        "kv_compact": kvc,
+        "achievable": achievable,
         "gemm_mfma": {"flops_per_step": gemm_flops, "ms_per_step": round(gemm_ms, 4),
                       "achieved": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms else None, "peak": mfma_peak, "unit": "TFLOP/s",
                       "util": round(gemm_flops / (gemm_ms * 1e-3) / 1e12 / mfma_peak, 5) if gemm_ms else None,

@@ -125,6 +125,20 @@ enum {
 int fs_stage_profile_begin(fs_stage *stage, int max_records);
 int fs_stage_profile_end(fs_stage *stage, void *stream, double *total_ms, long long *counts);
 
+/*
+ * Measurement aids (not part of the method): what one launch reaches on this machine, for pricing the kernels against
+ * an achievable peak beside the datasheet one.  Both wait for their own launches (HIP events) and are not capturable.
+ *   fs_probe_stream_read  one-pass read of bytes_per_launch bytes (a multiple of 256 KiB, >= 1 MiB) with the access
+ *                         pattern of the projection kernels' weight stream; consecutive launches rotate through
+ *                         buf[0, buf_bytes) (device, 16-byte aligned, >= bytes_per_launch + 64; give several times the
+ *                         last-level cache so that no launch finds its data cached).  Result: GB/s of one launch.
+ *   fs_probe_mfma_bf16    register-resident loop of independent 16x16x32 bf16 MFMAs on every SIMD; scratch: >= 4 device
+ *                         bytes.  Result: TFLOP/s.
+ * Errors: FS_EINVAL, FS_EHIP.
+ */
+int fs_probe_stream_read(const void *buf, size_t buf_bytes, size_t bytes_per_launch, int launches, void *stream, double *gb_per_s);
+int fs_probe_mfma_bf16(void *scratch, int launches, void *stream, double *tflop_per_s);
+
 /* hipError_t (as int) behind the most recent FS_EHIP on the calling thread, 0 if none. */
 int fs_last_hip_error(void);
 

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflowspec_hip.so")
-SOURCES = ("api.hip", "gemm.hip", "attention.hip", "tree.hip", "sample.hip", "tree_host.cpp")
+SOURCES = ("api.hip", "gemm.hip", "attention.hip", "tree.hip", "sample.hip", "probe.hip", "tree_host.cpp")
 EXTRA = os.environ.get("FLOWSPEC_CXXFLAGS", "").split()
 FLAGS = EXTRA + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -26,7 +26,7 @@ KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "ar
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
            "fs_stage_profile_end", "fs_tree_verify_stage",
            "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
-           "fs_tree_prune", "fs_tree_merge")
+           "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16")
 
 
 class FlowSpecError(RuntimeError):
@@ -85,6 +85,8 @@ def _load():
     lib.fs_tree_segment.argtypes = [vp, vp, vp, ci, ci, vp, vp, vp, vp]
     lib.fs_tree_prune.argtypes = [vp, vp, ci, vp, ci, ci, vp, vp]
     lib.fs_tree_merge.argtypes = [vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.fs_probe_stream_read.argtypes = [vp, C.c_size_t, C.c_size_t, ci, vp, C.POINTER(C.c_double)]
+    lib.fs_probe_mfma_bf16.argtypes = [vp, ci, vp, C.POINTER(C.c_double)]
     for n in EXPORTS:
         if n not in ("fs_stage_workspace_bytes",):
             getattr(lib, n).restype = C.c_int
@@ -217,6 +219,21 @@ def new_accept_buffers(T, n_ver_max, device="cuda"):
     retain = torch.zeros(max(T, 1), dtype=torch.int32, device=device)
     work = torch.zeros(2 * max(n_ver_max, 1) * FS_ARGMAX_CHUNKS, dtype=torch.int32, device=device)
     return res, retain, work
+
+
+def probe_stream_read(buf, bytes_per_launch, launches=20, stream=None) -> float:
+    """GB/s of a one-pass read of bytes_per_launch bytes, rotating through the device tensor `buf` (measurement aid)."""
+    out = C.c_double()
+    _check(_lib.fs_probe_stream_read(_dp(buf), C.c_size_t(buf.numel() * buf.element_size()), C.c_size_t(int(bytes_per_launch)), int(launches),
+                                     _stream(stream), C.byref(out)), "fs_probe_stream_read")
+    return out.value
+
+
+def probe_mfma_bf16(scratch, launches=5, stream=None) -> float:
+    """TFLOP/s of a register-resident bf16 MFMA loop (measurement aid)."""
+    out = C.c_double()
+    _check(_lib.fs_probe_mfma_bf16(_dp(scratch), int(launches), _stream(stream), C.byref(out)), "fs_probe_mfma_bf16")
+    return out.value
 
 
 def tree_accept(logits, amax, token, parent, n_ver, res, retain, work=None, stream=None):

@@ -18,7 +18,7 @@ def _fs():
 def test_every_declared_symbol_is_exported():
     fs = _fs()
     hdr = open(os.path.join(ROOT, "include", "flowspec.h")).read()
-    declared = set(re.findall(r"\b(fs_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(fs_[a-z_0-9]+)\s*\(", hdr))
     assert declared == set(fs.EXPORTS)
     for name in declared:
         assert hasattr(fs.lib(), name), name
