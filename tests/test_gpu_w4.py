@@ -73,6 +73,19 @@ def test_w4_13b_shape_two_layers():
     assert np.array_equal(am.cpu().numpy()[clear], lo.argmax(axis=1)[clear])
 
 
+def test_w4_many_row_chain():
+    """A 200-row chain in one segment with 4-bit weights (row blocks of the few-row kernel)."""
+    from tests.gpu_util import TOL, Pair, max_rel_err
+    cfg = synth.StageConfig("w4-chain", "bf16", 2, 512, 4, 4, 128, 1408, 0, 60, 200, 200, 200, 1)
+    print("case w4 chain 200 rows", flush=True)
+    pair = Pair(cfg, seed=8, w4=True)
+    hid = synth.hidden(cfg, 200, 0, 8)
+    o, g = pair.verify_tree(np.arange(-1, 199, dtype=np.int32), hid, 200)
+    err = max_rel_err(g, o)
+    print(f"  hidden max-rel-err {err:.3e}", flush=True)
+    assert err < TOL["bf16"]
+
+
 def test_w4_rejects_f32_and_bad_shapes():
     from paper_2507_02620_amd import flowspec as fs
     with pytest.raises(fs.FlowSpecError):
