@@ -12,7 +12,9 @@ LIB = os.path.join(HERE, "libflowspec_hip.so")
 SOURCES = ("api.hip", "gemm.hip", "attention.hip", "tree.hip", "sample.hip", "probe.hip", "tree_host.cpp")
 EXTRA = os.environ.get("FLOWSPEC_CXXFLAGS", "").split()
 FLAGS = EXTRA + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # leading scalar kernel arguments arrive in SGPRs with the wave instead of through a scalar load
+         "-mllvm", "-amdgpu-kernarg-preload-count=8"]
 
 
 def _run(cmd):

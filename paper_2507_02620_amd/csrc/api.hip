@@ -58,22 +58,25 @@ int env_int(const char* name, int dflt) {
 
 // Tiles per group: the largest allowed NT that still leaves about two workgroups per compute unit;
 // segments longer than 16 rows prefer NT >= 2 so that activation re-reads through L2 stay below the weight stream.
-int choose_nt(int tiles, bool pair, int max_seg, const char* env) {
+int choose_nt(int tiles, bool pair, int max_seg, const char* env, bool wide_n = false) {
     int nt = pair ? 2 : 1;
     if (tiles / 4 >= 512) nt = 4;
     else if (tiles / 2 >= 512) nt = 2;
     if (max_seg > 16 && nt < 2 && tiles / 2 >= 160) nt = 2;
+    // segments of more than 32 rows: QKV and the LM head do better with 4 tiles per group (measured at 64 rows: QKV 42 -> 34 us,
+    // head 92 -> 67 us; gate/up and the d_model-wide projections do not)
+    if (max_seg > 32 && wide_n && tiles / 4 >= 160) nt = 4;
     int o = env_int(env, 0);
     if (o == 1 || o == 2 || o == 4) nt = (pair && o == 1) ? 2 : o;
     return nt;
 }
 
-void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, const char* env_nt, int w4 = 0) {
+void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, const char* env_nt, int w4 = 0, bool wide_n = false) {
     const int KT = 64 / elem;  // 32 for bf16, 16 for f32
     g.K = K;
     g.w4 = w4;
     g.nkt = (K + KT - 1) / KT;
-    g.NT = choose_nt(tiles, pair, max_seg, env_nt);
+    g.NT = choose_nt(tiles, pair, max_seg, env_nt, wide_n);
     if (w4) {
         // a 4-bit tile is a quarter of the bytes: larger groups keep the per-workgroup stream long enough;
         // 64-row segments stay at NT <= 2 (registers)
@@ -145,7 +148,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     for (int l = 0; l < d->n_layers; ++l) {
         LayerPlan& p = L.layers[l];
         const int qkv_tiles = (d->n_q_heads + 2 * d->n_kv_heads) * hd / 16;
-        plan_gemm(p.qkv, qkv_tiles, d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_QKV", w4);
+        plan_gemm(p.qkv, qkv_tiles, d->d_model, elem, true, d->max_seg, "FLOWSPEC_NT_QKV", w4, true);
         p.qkv.N = qkv_tiles * 16;
         plan_gemm(p.o, d->d_model / 16, nq, elem, false, d->max_seg, "FLOWSPEC_NT_O", w4);
         p.o.N = d->d_model;
@@ -160,7 +163,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
         p.qkv.bias = (float*)take((size_t)p.qkv.n_groups * p.qkv.NT * 16 * sizeof(float));
     }
     if (d->vocab > 0) {
-        plan_gemm(L.head, (d->vocab + 15) / 16, d->d_model, elem, false, d->max_seg, "FLOWSPEC_NT_HEAD", w4);
+        plan_gemm(L.head, (d->vocab + 15) / 16, d->d_model, elem, false, d->max_seg, "FLOWSPEC_NT_HEAD", w4, true);
         L.head.N = d->vocab;
         L.head.wp = (void*)take(L.head.bytes());
         L.head.sp = (void*)take(L.head.scale_bytes());
@@ -188,13 +191,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.off_sspb = take(ssp_bytes);
     // many-row segments: scratch for the K-split partial results of the two residual projections
     L.part_bytes = 0;
-    if (d->dtype == FS_BF16 && !w4 && d->max_seg >= 128) {
-        const int ms = d->max_seg, tiles = d->d_model / 16;
-        L.part_bytes = std::max(wide_partial_bytes(ms, tiles, wide_k_splits(ms, tiles, nq / 32)),
-                                wide_partial_bytes(ms, tiles, wide_k_splits(ms, tiles, d->d_ffn / 32)));
-        // shorter segments may want more slices of fewer rows: the launcher takes what fits
-        L.part_bytes = std::max(L.part_bytes, wide_partial_bytes(128, tiles, 8));
-    }
+    if (d->dtype == FS_BF16 && !w4 && d->max_seg >= 128) L.part_bytes = wide_partial_bytes(d->max_seg);
     L.off_part = take(L.part_bytes);
     L.off_ancall = take((size_t)d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // masks of every node while a deep tree's are built
     L.total = off;
@@ -499,7 +496,7 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     const bool handover = w4 || wide;
     float* sspa = st->at<float>(L.off_sspa);
     float* sspb = st->at<float>(L.off_sspb);
-    const int res_parts = wide ? (d.d_model / 16 + 15) / 16 * 4 : d.d_model / 16;  // partial sums per row a residual epilogue leaves
+    const int res_parts = wide ? wide_ssp_parts(l_s, d.d_model / 16) : d.d_model / 16;  // partial sums per row a residual epilogue leaves
     int ssp_n_first = 0;
     if (handover)
         HIP_TRY_K(st, FS_K_PREPARE, s,
@@ -556,14 +553,15 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     const GemmPlan& p = st->L.head;
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
-    if (p.w4) {  // gained copy of the rows + their sums of squares, as at the entry of a 4-bit stage
+    const bool wide = !p.w4 && st->d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
+    if (p.w4 || wide) {  // (gained) fragment-major copy of the rows + their sums of squares, as at the entry of such a stage
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);
-        const bf16_t* gain = st->at<bf16_t>(st->L.off_gain) + (size_t)(2 * st->d.n_layers) * st->d.d_model;
+        const bf16_t* gain = p.w4 ? st->at<bf16_t>(st->L.off_gain) + (size_t)(2 * st->d.n_layers) * st->d.d_model : nullptr;
         HIP_TRY_K(st, FS_K_PREPARE, s, launch_prenorm(hidden, st->d.d_model, l_s, st->d.d_model, gain, hb, ssp, st->L.ssp_stride, &g.ssp_n, s));
         g.X = hb; g.x_frag = 1; g.ssp_in = ssp; g.ssp_stride = st->L.ssp_stride;
     }
-    HIP_TRY_K(st, FS_K_HEAD, s, launch_proj(st, EPI_LOGITS, p, g, s));
+    HIP_TRY_K(st, FS_K_HEAD, s, launch_proj(st, EPI_LOGITS, p, g, s, wide));
     HIP_TRY_K(st, FS_K_ARGMAX, s, launch_argmax(logits, l_s, st->d.vocab, FS_ARGMAX_CHUNKS, st->at<int32_t>(st->L.off_amw), amax, s));
     return FS_OK;
 }

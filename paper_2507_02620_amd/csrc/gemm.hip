@@ -141,15 +141,41 @@ static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4
     constexpr bool NORM = (EPI != EPI_RESID);
     const int r16 = lane & 15, g = lane >> 4;
     // ---- cross-wave reduction through LDS ---------------------------------------------------------
-    float* red = (float*)smem;                       // [NW][MT*NT][4][64]
-    float* ssr = red + (size_t)NW * MT * NT * 256;   // [NW][MT][16]
+    // LDS holds NC = a.red_copies copies of the workgroup's tiles.  With more waves than copies, the last (up to NC) active
+    // waves hand their tiles to the first ones, round by round, until NC waves are left; those write their copies and the
+    // epilogue items add them up.  (Many-row tile shapes would otherwise have to run with fewer waves.)
+    constexpr bool ROUNDS = (MT * NT > 6);  // only then can the launcher pick fewer copies than waves (48 KiB / (MT*NT) KiB < 8)
+    const int NC = ROUNDS ? a.red_copies : NW;
+    float* red = (float*)smem;                       // [NC][MT*NT][4][64]
+    float* ssr = red + (size_t)NC * MT * NT * 256;   // [NW][MT][16]
+    auto put = [&](int slot) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[(((size_t)w * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane] = acc[mt][nt][v];
-        if (NORM) {
+                for (int v = 0; v < 4; ++v) red[(((size_t)slot * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane] = acc[mt][nt][v];
+    };
+    for (int active = NW; ROUNDS && active > NC;) {  // uniform
+        const int k = min(NC, active - NC);  // the top k active waves hand over to waves 0 .. k-1
+        if (w >= active - k && w < active) put(w - (active - k));
+        __syncthreads();
+        if (w < k) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[mt][nt][v] += red[(((size_t)w * MT * NT + mt * NT + nt) * 4 + v) * 64 + lane];
+        }
+        __syncthreads();
+        active -= k;
+    }
+    const int copies = ROUNDS ? (NW < NC ? NW : NC) : NW;
+    if (!ROUNDS || w < copies) put(w);
+    if (NORM) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
             float t = wave_xor_add(wave_xor_add(ss[mt], 16), 32);
             if (lane < 16) ssr[(w * MT + mt) * 16 + lane] = t;
         }
@@ -170,7 +196,7 @@ static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 float s = 0.f;
-                for (int ww = 0; ww < NW; ++ww) s += red[(((size_t)ww * MT * NT + mt * NT + ntp * TPI + t) * 4 + v) * 64 + lane];
+                for (int ww = 0; ww < copies; ++ww) s += red[(((size_t)ww * MT * NT + mt * NT + ntp * TPI + t) * 4 + v) * 64 + lane];
                 y[t][v] = s;
             }
         float rs = 1.f;
@@ -190,8 +216,11 @@ static __device__ __forceinline__ void reduce_and_store(const GemmArgs& a, f32x4
     }
 }
 
+// The values the first loads depend on travel as leading scalar kernel arguments: those can be preloaded into SGPRs with
+// the wave (compiler option -amdgpu-kernarg-preload-count), whereas the fields of the by-value struct are fetched from
+// the kernarg segment by a scalar load the whole prologue would have to wait for.
 template <typename T, int MT, int NT, int EPI>
-__global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
+__global__ void __launch_bounds__(512) skinny_gemm_kernel(const void* Wp, const void* X, int nkt_, int ldx_, int M_, int x_frag_, const GemmArgs a) {
     using E = Elem<T>;
     using frag_t = typename E::frag_t;
     constexpr bool NORM = (EPI != EPI_RESID);
@@ -204,19 +233,19 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
 
     // k-tiles are dealt to the waves round-robin (wave w takes w, w + NW, ...): at any moment the workgroup's
     // waves read neighbouring KiBs, so the group's weight block is swept front to back as one stream.
-    const int nsteps = (a.nkt - w + NW - 1) / NW;  // >= 1: the host never launches more waves than k-tiles
-    const unsigned char* wbase = (const unsigned char*)a.Wp + ((size_t)grp * a.nkt) * (size_t)(NT * 1024) + (size_t)lane * 16;
+    const int nsteps = (nkt_ - w + NW - 1) / NW;  // >= 1: the host never launches more waves than k-tiles
+    const unsigned char* wbase = (const unsigned char*)Wp + ((size_t)grp * nkt_) * (size_t)(NT * 1024) + (size_t)lane * 16;
     // Rows beyond M read row M-1 instead: their results are never stored, and the loop stays free of branches.
     // Fragment-major activations (padded to whole 16-row tiles) are addressed like the weights.
     const T* xrow[MT];
-    const size_t xstep = a.x_frag ? (size_t)64 * E::EPF : (size_t)E::KT;  // elements between consecutive k-tiles
+    const size_t xstep = x_frag_ ? (size_t)64 * E::EPF : (size_t)E::KT;  // elements between consecutive k-tiles
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        if (a.x_frag) {
-            xrow[mt] = (const T*)a.X + (((size_t)(mb * MT + mt) * a.nkt) * 64 + lane) * E::EPF;
+        if (x_frag_) {
+            xrow[mt] = (const T*)X + (((size_t)(mb * MT + mt) * nkt_) * 64 + lane) * E::EPF;
         } else {
-            const int m = min(row0 + mt * 16 + r16, a.M - 1);
-            xrow[mt] = (const T*)a.X + (size_t)m * a.ldx + g * E::EPF;
+            const int m = min(row0 + mt * 16 + r16, M_ - 1);
+            xrow[mt] = (const T*)X + (size_t)m * ldx_ + g * E::EPF;
         }
     }
 
@@ -269,12 +298,20 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const GemmArgs a) {
     reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0, resid_first);
 }
 
+// copies of the workgroup's tiles the cross-wave reduction keeps in LDS: as many as there are waves, within about 48 KiB
+static int reduction_copies(int nw, int mt, int nt) {
+    const int fit = 48 / (mt * nt);  // 1 KiB per tile and copy
+    return nw < fit ? nw : (fit < 1 ? 1 : fit);
+}
+
 template <typename T, int MT, int NT, int EPI>
-static hipError_t launch_one(int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+static hipError_t launch_one(int NW, int n_groups, const GemmArgs& a0, hipStream_t s) {
+    GemmArgs a = a0;
     const int mblocks = (a.M + MT * 16 - 1) / (MT * 16);
     if (NW > 8) NW = 8;
-    const size_t lds = (size_t)NW * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
-    hipLaunchKernelGGL((skinny_gemm_kernel<T, MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a);
+    a.red_copies = reduction_copies(NW, MT, NT);
+    const size_t lds = (size_t)a.red_copies * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
+    hipLaunchKernelGGL((skinny_gemm_kernel<T, MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a.Wp, a.X, a.nkt, a.ldx, a.M, a.x_frag, a);
     return hipGetLastError();
 }
 
@@ -292,9 +329,11 @@ static hipError_t launch_mt_nt(int MT, int NT, int NW, int n_groups, const GemmA
 }
 
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+    // 33 to 64 rows per block: 4 row tiles and at most 4 waves (several smaller workgroups per compute unit overlap each
+    // other's start-up and epilogue; 8 waves: QKV 42 -> 44 us, gate/up 50 -> 53 us at 64 rows).  Two 32-row blocks per
+    // group instead were slower as well (gate/up 54 -> 61 us).
     const int MT = a.M <= 16 ? 1 : (a.M <= 32 ? 2 : 4);
-    // LDS for the cross-wave reduction grows with NW*MT*NT KiB; keep it within 64 KiB
-    while (NW > 1 && (size_t)NW * MT * NT * 1024 > 60 * 1024) NW >>= 1;
+    if (MT == 4 && NW > 4) NW = 4;
 #define FS_EPI(e)                                                                      \
     if (epi == e) {                                                                    \
         if (dtype == 0) return launch_mt_nt<float, e>(MT, NT, NW, n_groups, a, s);     \
@@ -320,13 +359,15 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
 //     (GemmArgs::ssp_in), so the loop contains no per-element arithmetic.
 //   * Workgroups that share weights (the row blocks of one feature block) get consecutive slots on one XCD, so the
 //     weights are fetched from HBM once and hit in that XCD's L2 afterwards.
-constexpr int WIDE_WN_TILES = 4, WIDE_WAVES = 4, WIDE_PFW = 5;
 
 //   * Projections too narrow to fill the chip (d_model outputs, a few row blocks) split K over `k_splits` workgroups;
 //     each writes its raw accumulator tiles (MFMA lane order, so 16 bytes per lane, contiguous per wave) to a scratch
 //     array and wide_fixup_kernel adds them up and runs the residual epilogue.
-template <int EPI, bool PARTIAL, int BMT>
-__global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
+//   * The block shape is a template parameter.  64-row blocks with 2 waves x 2 tiles per workgroup were tried for segments of
+//     33 to 127 rows and lost to the few-row kernel (64 rows: QKV 37 -> 75 us, gate/up 49 -> 91 us): a wave then has only 8
+//     MFMAs per k-tile to hide a barrier and an LDS round trip behind.
+template <int EPI, bool PARTIAL, int BMT, int WNT, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
                                                            float* part) {
     using T = bf16_t;
     using E = Elem<T>;
@@ -334,8 +375,9 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
     constexpr bool NORM = (EPI != EPI_RESID);
     constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
     constexpr int TPI = PAIR ? 2 : 1;
-    constexpr int WNT = WIDE_WN_TILES, PFW = BMT == 4 ? WIDE_PFW - 1 : WIDE_PFW;
-    constexpr int XL = BMT / 4;  // 16-byte pieces of the activation stage per thread
+    constexpr int PFW = BMT == 8 ? 5 : 8;  // k-tiles of weights in flight per wave
+    constexpr int XL = BMT / WAVES;        // 16-byte pieces of the activation stage per thread
+    static_assert(BMT % WAVES == 0 && BMT % 4 == 0, "row tiles must split over the waves and over groups of 4");
     __shared__ __align__(16) unsigned char xs[2][BMT * 1024];
     __shared__ float rs_s[BMT * 16];
 
@@ -360,7 +402,7 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
     // this wave's weight tiles; tiles beyond the matrix re-read the last one (their results are never stored).
     // Addresses are a uniform base plus a 32-bit byte offset per lane (one matrix is far below 4 GiB), advanced by one
     // k-tile per fetch until the last k-tile of the slice is reached.
-    const int pt0 = (col * WIDE_WAVES + w) * WNT;
+    const int pt0 = (col * WAVES + w) * WNT;
     const unsigned char* wbase = (const unsigned char*)a.Wp;
     const unsigned char* xbase = (const unsigned char*)a.X;
     unsigned woff[WNT], xoff[XL];
@@ -370,10 +412,10 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
         woff[nt] = (unsigned)((((size_t)(pc / layout_nt) * a.nkt + kt_lo) * layout_nt + pc % layout_nt) * 1024 + (size_t)lane * 16);
     }
     const unsigned wstep = (unsigned)layout_nt * 1024;
-    // this thread's 16-byte pieces of the activation stage: fragments w (and w + 4) of the block's BMT
+    // this thread's 16-byte pieces of the activation stage: fragments w, w + WAVES, ... of the block's BMT
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
-        const int mt = min(mt0 + w + 4 * i, m_tiles - 1);
+        const int mt = min(mt0 + w + WAVES * i, m_tiles - 1);
         xoff[i] = (unsigned)((((size_t)mt * a.nkt + kt_lo) * 64 + lane) * 16);
     }
     const unsigned xstep = 1024;
@@ -402,7 +444,7 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
     };
     auto store_x = [&](int j, int buf) {
 #pragma unroll
-        for (int i = 0; i < XL; ++i) *(frag_t*)(xs[buf] + (size_t)(w + 4 * i) * 1024 + (size_t)lane * 16) = xr[j][i];
+        for (int i = 0; i < XL; ++i) *(frag_t*)(xs[buf] + (size_t)(w + WAVES * i) * 1024 + (size_t)lane * 16) = xr[j][i];
     };
     // Pipeline, k-tile kt: weights in wq[kt % PFW] (fetched PFW k-tiles ahead: the weight fetch is the longest latency in the
     // loop), activations in LDS buffer kt & 1; xr[(kt + 1) & 1] holds k-tile kt + 1 and xr[kt & 1] k-tile kt + 2 when the
@@ -442,7 +484,7 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
 
     if constexpr (PARTIAL) {
         // raw tiles: part[ks][m tile][n tile][lane] (f32x4); tiles beyond the matrix are dropped
-        const int nt_all = n_cols * WIDE_WAVES * WNT;
+        const int nt_all = n_cols * WAVES * WNT;
 #pragma unroll
         for (int mt = 0; mt < BMT; ++mt) {
             if (mt0 + mt >= m_tiles) break;
@@ -468,27 +510,27 @@ __global__ void __launch_bounds__(256, BMT == 4 ? 3 : 2) wide_gemm_kernel(const 
             hsq += epilogue_item<T, EPI>(a, y, rs, m, pt0 + ntp * TPI, g);
         }
         if constexpr (EPI == EPI_RESID) {
-            if (a.ssp_out) {  // one partial sum per wave (64 features) and row
+            if (a.ssp_out) {  // one partial sum per wave (its WNT tiles) and row
                 hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
-                if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)(col * WIDE_WAVES + w) * a.ssp_stride + m] = hsq;
+                if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)(col * WAVES + w) * a.ssp_stride + m] = hsq;
             }
         }
     }
 }
 
-// Sum of the K slices' raw tiles + residual epilogue.  One wave per (row tile, 4 feature tiles): the same lane layout
-// as the accumulators, the same partial sums of squares as the direct epilogue.
-__global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n_cols, int k_splits, const float* part) {
+// Sum of the K slices' raw tiles + residual epilogue.  One wave per (row tile, group of wnt feature tiles = what one
+// wave of the projection kernel owns): the same lane layout as the accumulators, the same partial sums of squares as the
+// direct epilogue.
+__global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int nt_all, int wnt, int k_splits, const float* part) {
     const int lane = threadIdx.x & 63, r16 = lane & 15, g = lane >> 4;
-    const int m_tiles = (a.M + 15) >> 4, nt_all = n_cols * WIDE_WAVES * WIDE_WN_TILES, quads = nt_all / WIDE_WN_TILES;
-    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);  // (row tile, quad of feature tiles)
-    if (unit >= m_tiles * quads) return;
-    const int mt = unit / quads, quad = unit % quads;
+    const int m_tiles = (a.M + 15) >> 4, groups = nt_all / wnt;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= m_tiles * groups) return;
+    const int mt = unit / groups, grp = unit % groups;
     const int m = mt * 16 + r16;
     float hsq = 0.f;
-#pragma unroll
-    for (int nt = 0; nt < WIDE_WN_TILES; ++nt) {
-        const int ptile = quad * WIDE_WN_TILES + nt;
+    for (int nt = 0; nt < wnt; ++nt) {
+        const int ptile = grp * wnt + nt;
         f32x4 sum{0.f, 0.f, 0.f, 0.f};
         for (int ks = 0; ks < k_splits; ++ks) sum += ((const f32x4*)part)[(((size_t)ks * m_tiles + mt) * nt_all + ptile) * 64 + lane];
         const float y[1][4] = {{sum[0], sum[1], sum[2], sum[3]}};
@@ -496,63 +538,76 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
     }
     if (a.ssp_out) {
         hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
-        if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)quad * a.ssp_stride + m] = hsq;
+        if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)grp * a.ssp_stride + m] = hsq;
     }
 }
 
-// Row tiles per block: 8 (128 rows: each weight fragment feeds 8 MFMAs).  Blocks of 4 row tiles double the number of
-// workgroups but halve the reuse of a weight fragment; measured slower at every shape tried (512 rows: gate/up 131 -> 169 us,
-// 1024 rows: 228 -> 318 us), so they are only reachable through FLOWSPEC_WIDE_BMT=4 (for experiments).
-int wide_bmt(int, int) {
-    static const int forced = [] { const char* v = getenv("FLOWSPEC_WIDE_BMT"); return v ? atoi(v) : 0; }();
-    return forced == 4 ? 4 : 8;
-}
+// Block geometry by projection kind and row count (see the kernel's header comment).
+struct WideShape {
+    int bmt, wnt, waves;
+};
+static WideShape wide_shape(int, int) { return {8, 4, 4}; }
 
-int wide_k_splits(int M, int n_tiles, int nkt) {
-    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
-    const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
-    const int bm = wide_bmt(M, n_tiles) * 16;
-    const int m_blocks = (M + bm - 1) / bm;
-    int s = 1;
-    while (s < 8 && n_cols * m_blocks * s * 2 <= 512 && nkt / (s * 2) >= 8) s *= 2;  // about two workgroups per compute unit
-    return s;
-}
-
-size_t wide_partial_bytes(int M, int n_tiles, int k_splits) {
-    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
-    const size_t nt_all = (size_t)((n_tiles + col_tiles - 1) / col_tiles) * col_tiles;
-    return (size_t)k_splits * ((M + 15) / 16) * nt_all * 1024;
-}
-
-template <int BMT>
-static hipError_t launch_wide_bmt(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
-    const int col_tiles = WIDE_WAVES * WIDE_WN_TILES;
-    const int n_cols = (n_tiles + col_tiles - 1) / col_tiles;
-    const int m_blocks = (a.M + BMT * 16 - 1) / (BMT * 16);
-    int ks = 1;
-    if (epi == EPI_RESID && part) {
-        ks = wide_k_splits(a.M, n_tiles, a.nkt);
-        while (ks > 1 && wide_partial_bytes(a.M, n_tiles, ks) > part_bytes) ks >>= 1;
+struct WideGrid {
+    int n_cols, m_blocks, k_splits;
+};
+// K slices for the d_model-wide residual projections: until there are about two workgroups per compute unit, at least 8
+// k-tiles per slice, and no more than the scratch array holds.
+static WideGrid wide_grid(const WideShape& sh, int epi, int M, int n_tiles, int nkt, size_t part_bytes) {
+    WideGrid g;
+    const int col_tiles = sh.waves * sh.wnt;
+    g.n_cols = (n_tiles + col_tiles - 1) / col_tiles;
+    g.m_blocks = (M + sh.bmt * 16 - 1) / (sh.bmt * 16);
+    g.k_splits = 1;
+    if (epi == EPI_RESID) {
+        const size_t per_split = (size_t)((M + 15) / 16) * g.n_cols * col_tiles * 1024;
+        while (g.k_splits < 8 && g.n_cols * g.m_blocks * g.k_splits * 2 <= 512 && nkt / (g.k_splits * 2) >= 8 &&
+               per_split * g.k_splits * 2 <= part_bytes)
+            g.k_splits *= 2;
     }
-    const int grid = (n_cols + 7) / 8 * 8 * m_blocks * ks;
-    if (epi == EPI_QKV)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_QKV, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
-    else if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_SWIGLU, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
-    else if (ks == 1)
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, false, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
-    else {
-        hipLaunchKernelGGL((wide_gemm_kernel<EPI_RESID, true, BMT>), dim3(grid), dim3(256), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, ks, part);
-        const int units = ((a.M + 15) / 16) * n_cols * WIDE_WAVES;
-        hipLaunchKernelGGL(wide_fixup_kernel, dim3((units + 3) / 4), dim3(256), 0, s, a, n_cols, ks, part);
+    return g;
+}
+
+int wide_ssp_parts(int M, int n_tiles) {
+    const WideShape sh = wide_shape(EPI_RESID, M);
+    const int col_tiles = sh.waves * sh.wnt;
+    return (n_tiles + col_tiles - 1) / col_tiles * sh.waves;
+}
+
+size_t wide_partial_bytes(int max_rows) {
+    // slices * row tiles * feature tiles KiB, with slices * blocks <= 512: at most 512 blocks' worth of tiles
+    const WideShape sh = wide_shape(EPI_RESID, max_rows);
+    return (size_t)512 * sh.bmt * sh.waves * sh.wnt * 1024;
+}
+
+template <int EPI, int BMT, int WNT, int WAVES>
+static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
+    const WideShape sh{BMT, WNT, WAVES};
+    const WideGrid g = wide_grid(sh, EPI, a.M, n_tiles, a.nkt, part ? part_bytes : 0);
+    const int grid = (g.n_cols + 7) / 8 * 8 * g.m_blocks * g.k_splits;
+    if constexpr (EPI == EPI_RESID) {
+        if (g.k_splits > 1) {
+            hipLaunchKernelGGL((wide_gemm_kernel<EPI, true, BMT, WNT, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
+                               g.m_blocks, g.k_splits, part);
+            const int units = ((a.M + 15) / 16) * g.n_cols * WAVES;
+            hipLaunchKernelGGL(wide_fixup_kernel, dim3((units + 3) / 4), dim3(256), 0, s, a, g.n_cols * WAVES * WNT, WNT, g.k_splits, part);
+            return hipGetLastError();
+        }
     }
+    hipLaunchKernelGGL((wide_gemm_kernel<EPI, false, BMT, WNT, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
+                       g.m_blocks, 1, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
-    if (epi == EPI_LOGITS || !a.x_frag) return hipErrorInvalidValue;
-    if (wide_bmt(a.M, n_tiles) == 4) return launch_wide_bmt<4>(epi, layout_nt, n_tiles, a, part, part_bytes, s);
-    return launch_wide_bmt<8>(epi, layout_nt, n_tiles, a, part, part_bytes, s);
+    if (!a.x_frag) return hipErrorInvalidValue;
+    switch (epi) {
+        case EPI_QKV: return launch_wide_shape<EPI_QKV, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_SWIGLU: return launch_wide_shape<EPI_SWIGLU, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_RESID: return launch_wide_shape<EPI_RESID, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_LOGITS: return launch_wide_shape<EPI_LOGITS, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 // ---- 4-bit weights (W4A16) ------------------------------------------------------------------------
@@ -684,9 +739,11 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
 }
 
 template <int MT, int NT, int EPI>
-static hipError_t launch_one_w4(int NW, int n_groups, const GemmArgs& a, hipStream_t s) {
+static hipError_t launch_one_w4(int NW, int n_groups, const GemmArgs& a0, hipStream_t s) {
+    GemmArgs a = a0;
     const int mblocks = (a.M + MT * 16 - 1) / (MT * 16);
-    const size_t lds = (size_t)NW * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
+    a.red_copies = reduction_copies(NW, MT, NT);
+    const size_t lds = (size_t)a.red_copies * MT * NT * 1024 + (size_t)NW * MT * 16 * sizeof(float);
     hipLaunchKernelGGL((skinny_gemm_w4_kernel<MT, NT, EPI>), dim3(n_groups, mblocks), dim3(NW * 64), lds, s, a);
     return hipGetLastError();
 }
@@ -709,7 +766,6 @@ hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs&
     // the quarter-size weights mostly hits in L2
     const int MT = a.M <= 16 ? 1 : 2;
     if (NW > 8) NW = 8;
-    while (NW > 1 && (size_t)NW * MT * NT * 1024 > 60 * 1024) NW >>= 1;
     if (epi == EPI_QKV) return launch_mt_nt_w4<EPI_QKV>(MT, NT, NW, n_groups, a, s);
     if (epi == EPI_RESID) return launch_mt_nt_w4<EPI_RESID>(MT, NT, NW, n_groups, a, s);
     if (epi == EPI_SWIGLU) return launch_mt_nt_w4<EPI_SWIGLU>(MT, NT, NW, n_groups, a, s);

@@ -24,6 +24,7 @@ struct GemmArgs {
     const float* ssp_in;   // [ssp_n][ssp_stride]: partial sums of squares per row
     int ssp_n, ssp_stride;
     int ldx, M, K, nkt;
+    int red_copies;  // set by the launcher: copies of the workgroup's tiles the cross-wave reduction keeps in LDS
     int N;           // valid output features (packed order)
     float eps;
     const float* bias;  // packed order, or null
@@ -82,12 +83,12 @@ hipError_t launch_prenorm(const void* X, int ldx, int M, int K, const void* gain
                              hipStream_t s);
 // 4-bit weights, bf16 activations: w[n][k] = scale[n][k/128] * (code - 8)
 hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);
-// bf16, fragment-major activations, QKV / RESID / SWIGLU: the kernel for segments of 128 rows and more.  layout_nt and
-// n_tiles describe the re-tiled weights (tiles per group, 16-feature tiles in total); normed projections need ssp_in.
-// `part` (may be null) is scratch for K-split partial results of narrow residual projections: the split count is the
-// largest that fits part_bytes (see wide_partial_bytes; wide_k_splits gives the count the launcher would like).
-int wide_k_splits(int M, int n_tiles, int nkt);
-size_t wide_partial_bytes(int M, int n_tiles, int k_splits);
+// bf16, fragment-major activations: the kernel for segments of 128 rows and more (128-row blocks).  layout_nt and n_tiles describe the re-tiled weights (tiles per group, 16-feature tiles in total);
+// normed projections need ssp_in.  `part` (may be null) is scratch for K-split partial results of the d_model-wide
+// residual projections (wide_partial_bytes gives a sufficient size for segments of up to max_rows rows); a residual
+// projection leaves wide_ssp_parts(M, n_tiles) partial sums of squares per row in ssp_out.
+int wide_ssp_parts(int M, int n_tiles);
+size_t wide_partial_bytes(int max_rows);
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s);
 // MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);
