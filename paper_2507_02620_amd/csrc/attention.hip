@@ -156,8 +156,8 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         const int s0 = tile * BS;
         __syncthreads();  // previous tile fully consumed
         stash();
+        if (tile + 1 < t1) fetch(tile + 1);  // in flight across the barrier and while this tile is computed
         __syncthreads();
-        if (tile + 1 < t1) fetch(tile + 1);  // in flight while this tile is computed
         if (!computes) continue;
 
         // ---- visibility of the tile's slots for this lane's rows: bit b <-> slot s0 + b --------------------------
