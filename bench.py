@@ -39,6 +39,17 @@ def read_traffic(path):
     return None
 
 
+def read_profile_avg_us(path, kernel_prefix):
+    """avg_us of the first kernel line starting with kernel_prefix in a committed rocprofv3 kernel-trace summary, or None."""
+    try:
+        for line in open(path):
+            if line.startswith(kernel_prefix):
+                return float(line[len(kernel_prefix):].split()[1])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -269,6 +280,19 @@ def main():
                                    "achieved_GBs": round(bytes_b / (ms_b * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                                    "frac": round(bytes_b / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del stage_b, kv_b, lw_b
+
+    # the same kernel's average duration in the committed rocprofv3 kernel trace (tool timestamps, without the two event
+    # records that bracket every launch of the live measurement and add about 2 us to it)
+    prof_us = None
+    if wide and args.workload == "P2":
+        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "wide_gemm_p2_kernel_trace.txt"), "void wide_gemm_kernel<2, false, 8, 4, 4>")
+    elif not wide and not w4 and args.workload == "C2":
+        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "bench_c2_kernel_trace.txt"), "void skinny_gemm_kernel<bool _Accum, int, E, 2, 2>")
+    if prof_us:
+        roofline["rocprof_avg_launch_us"] = prof_us
+        work = roofline.get("algorithmic_bytes", roofline.get("algorithmic_flops"))
+        scale = 1e9 if roofline["bound"] == "hbm" else 1e12
+        roofline["rocprof_frac"] = round(work / (prof_us * 1e-6) / scale / roofline["peak"], 4)
 
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
