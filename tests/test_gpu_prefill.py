@@ -17,6 +17,8 @@ def _chain(n):
     (synth.StageConfig("pf-bf16-mha128", "bf16", 1, 1024, 8, 8, 128, 2816, 0, 77, 512, 512, 512, 1), 512),
     (synth.StageConfig("pf-f32", "f32", 1, 256, 4, 4, 64, 688, 0, 50, 130, 130, 130, 1), 130),
     (synth.StageConfig("pf-bf16-1024", "bf16", 1, 512, 4, 4, 128, 1024, 0, 0, 1024, 1024, 1024, 1), 1024),
+    # feature counts that are not multiples of a workgroup's 256 features: padding tiles in every epilogue and in the K-split fix-up
+    (synth.StageConfig("pf-bf16-odd-widths", "bf16", 2, 480, 6, 3, 64, 1056, 0, 33, 150, 150, 150, 1, qkv_bias=True), 150),
 ])
 def test_chain_segment(cfg, rows):
     from tests.gpu_util import TOL, Pair, max_rel_err
