@@ -160,6 +160,25 @@ int fs_tree_verify_stage(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache
                          const int32_t *parent, void *hidden_out, void *stream);
 
 /*
+ * The same forward for a batch of requests that share the stage's weights (data-parallel serving: each request has its own
+ * KV cache, tree and context length): the segments' rows are stacked, the projections run once over all of them — the
+ * weights are streamed once per batch instead of once per request, and from 128 stacked rows on the projections are bound
+ * by the matrix units instead of by the weight stream — and tree attention runs per request inside the same launches.
+ *   items       HOST array [n_items]; each item is one fs_tree_verify_stage call's worth of arguments (kv, l_glo, l_cache,
+ *               seg_off, l_s, host parent array); l_s = 0 items are skipped.  All caches must share one set of strides.
+ *   hidden_in / hidden_out  device [sum of l_s, d_model], the items' rows in item order; may alias
+ * Every item is validated before anything is enqueued.  Errors: as fs_tree_verify_stage; FS_ECAP also when n_items >
+ * FS_MAX_BATCH or the stacked rows exceed max_seg; FS_EINVAL when the caches' strides differ.
+ */
+#define FS_MAX_BATCH 32
+typedef struct {
+    fs_kv_cache kv;
+    int l_glo, l_cache, seg_off, l_s;
+    const int32_t *parent; /* HOST [seg_off + l_s] */
+} fs_batch_item;
+int fs_tree_verify_batch(fs_stage *stage, const fs_batch_item *items, int n_items, const void *hidden_in, void *hidden_out, void *stream);
+
+/*
  * Last stage's verification output (Sec. III-A, continuous SD step: the next-token distribution sent to the
  * draft stage): logits = RMSNorm_final(hidden) * E^T in fp32 and their per-row argmax (lowest index on ties).
  *   hidden device [l_s, d_model]; logits device fp32 [l_s, vocab]; amax device int32 [l_s].

@@ -100,7 +100,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     std::vector<LayerPlan> layers;
     GemmPlan head;
-    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, off_gain, off_sspa, off_sspb, off_part, part_bytes, off_ancall, total;
+    size_t off_q, off_o, off_h, off_hb, off_act, off_anc, off_rope, off_po, off_pml, off_amw, off_invf, off_gain, off_sspa, off_sspb, off_part, part_bytes, off_ancall, off_krow, total;
     int ssp_stride;
 };
 
@@ -193,6 +193,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.part_bytes = 0;
     if (d->dtype == FS_BF16 && !w4 && d->max_seg >= 128) L.part_bytes = wide_partial_bytes(d->max_seg);
     L.off_part = take(L.part_bytes);
+    L.off_krow = take(M * sizeof(unsigned long long));  // cache slot address of every stacked row
     L.off_ancall = take((size_t)d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // masks of every node while a deep tree's are built
     L.total = off;
 }
@@ -439,33 +440,46 @@ static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, Ge
     return launch_gemm(st->d.dtype, epi, p.NT, p.NW, p.n_groups, g, s);
 }
 
-int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const void* hidden_in, int seg_off, int l_s, const int32_t* parent,
-                         void* hidden_out, void* stream) {
-    if (!st || l_s < 0 || seg_off < 0 || l_glo < 0) return FS_EINVAL;
-    if (l_cache != l_glo + seg_off) return FS_EINVAL;
-    if (l_s == 0) return FS_OK;
-    if (!hidden_in || !hidden_out || !parent) return FS_EINVAL;
+// The forward of one batch: every request's segment is prepared on its own (tree mask, positions, cache slots), then the
+// layers run over the stacked rows — projections once for all rows, attention per request inside one launch.
+static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const void* hidden_in, void* hidden_out, void* stream) {
+    if (!st || !items || n < 1) return FS_EINVAL;
+    if (n > FS_MAX_BATCH) return FS_ECAP;
     const fs_stage_desc& d = st->d;
-    const int T = seg_off + l_s;
-    if (T > d.max_tree || l_s > d.max_seg) return FS_ECAP;
-    if ((long long)l_cache + l_s > d.kv_capacity) return FS_ECAP;
-    int rc = valid_kv(d, kv);
-    if (rc) return rc;
-    if (parent[0] != -1) return FS_ETOPO;
-    short depth[FS_MAX_TREE];
-    int max_depth = 0;
-    depth[0] = 0;
-    for (int i = 1; i < T; ++i) {
-        if (parent[i] < -1 || parent[i] >= i) return FS_ETOPO;
-        depth[i] = parent[i] < 0 ? 0 : (short)(depth[parent[i]] + 1);
-        if (depth[i] > max_depth) max_depth = depth[i];
+    const Layout& L = st->L;
+    // ---- validation of every item before anything is enqueued ----
+    int rows = 0, max_M = 0, max_L = 0, n_live = 0;
+    const fs_kv_cache* kv0 = nullptr;
+    for (int i = 0; i < n; ++i) {
+        const fs_batch_item& it = items[i];
+        if (it.l_s < 0 || it.seg_off < 0 || it.l_glo < 0) return FS_EINVAL;
+        if (it.l_cache != it.l_glo + it.seg_off) return FS_EINVAL;
+        if (it.l_s == 0) continue;
+        if (!it.parent) return FS_EINVAL;
+        const int T = it.seg_off + it.l_s;
+        if (T > d.max_tree) return FS_ECAP;
+        if ((long long)it.l_cache + it.l_s > d.kv_capacity) return FS_ECAP;
+        int rc = valid_kv(d, it.kv);
+        if (rc) return rc;
+        if (!kv0) kv0 = &it.kv;
+        // one launch addresses every request's cache with the same strides
+        if (it.kv.stride_layer != kv0->stride_layer || it.kv.stride_kv != kv0->stride_kv || it.kv.stride_head != kv0->stride_head ||
+            it.kv.stride_tok != kv0->stride_tok)
+            return FS_EINVAL;
+        if (it.parent[0] != -1) return FS_ETOPO;
+        for (int j = 1; j < T; ++j)
+            if (it.parent[j] < -1 || it.parent[j] >= j) return FS_ETOPO;
+        rows += it.l_s;
+        max_M = std::max(max_M, it.l_s);
+        max_L = std::max(max_L, it.l_cache + it.l_s);
+        ++n_live;
     }
-    IdxList pl;
-    rc = fill_idx(pl, parent, T);
-    if (rc) return rc;
+    if (rows == 0) return FS_OK;
+    if (rows > d.max_seg) return FS_ECAP;
+    if (!hidden_in || !hidden_out) return FS_EINVAL;
+
     hipStream_t s = (hipStream_t)stream;
     const int hd = d.head_dim, nq = d.n_q_heads * hd, G = d.n_q_heads / d.n_kv_heads;
-    const Layout& L = st->L;
     void* q = st->at<void>(L.off_q);
     void* o = st->at<void>(L.off_o);
     float* h = st->at<float>(L.off_h);
@@ -473,24 +487,50 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     void* act = st->at<void>(L.off_act);
     uint64_t* anc = st->at<uint64_t>(L.off_anc);
     float2* rope = st->at<float2>(L.off_rope);
+    unsigned long long* krow = st->at<unsigned long long>(L.off_krow);
     const bf16_t* gains = st->at<bf16_t>(L.off_gain);
 
-    HIP_TRY_K(st, FS_K_PREPARE, s, launch_tree_prepare(pl, max_depth, l_glo, seg_off, l_s, hd, st->at<double>(L.off_invf), st->at<uint64_t>(L.off_ancall), anc, rope, s));
-
     AttnArgs at{};
-    at.q = q; at.o = o; at.M = l_s; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
-    at.l_glo = l_glo; at.L = l_cache + l_s; at.anc = anc;
+    at.q = q; at.o = o; at.Hq = d.n_q_heads; at.Hkv = d.n_kv_heads; at.hd = hd; at.G = G;
+    at.anc = anc;
     at.scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
-    at.stride_kv = kv.stride_kv; at.stride_head = kv.stride_head; at.stride_tok = kv.stride_tok;
+    at.stride_kv = kv0->stride_kv; at.stride_head = kv0->stride_head; at.stride_tok = kv0->stride_tok;
     at.part_o = st->at<float>(L.off_po); at.part_ml = st->at<float>(L.off_pml);
-    at.Rpad = (int)align_up((size_t)G * l_s, 16);
+    at.n_req = n_live; at.rows = rows; at.max_M = max_M; at.max_L = max_L;
+    at.Rpad = (int)align_up((size_t)G * rows, 16);
+
+    // ---- per request: ancestor masks, positions (rotary table) and cache slots of its rows, into the stacked arrays ----
+    int row0 = 0, rq = 0;
+    for (int i = 0; i < n; ++i) {
+        const fs_batch_item& it = items[i];
+        if (it.l_s == 0) continue;
+        const int T = it.seg_off + it.l_s;
+        short depth[FS_MAX_TREE];
+        int max_depth = 0;
+        depth[0] = 0;
+        for (int j = 1; j < T; ++j) {
+            depth[j] = it.parent[j] < 0 ? 0 : (short)(depth[it.parent[j]] + 1);
+            if (depth[j] > max_depth) max_depth = depth[j];
+        }
+        IdxList pl;
+        int rc = fill_idx(pl, it.parent, T);
+        if (rc) return rc;
+        KRowArgs kr{krow + row0, (unsigned long long)(uintptr_t)it.kv.base, (unsigned long long)it.kv.stride_tok * st->elem, it.l_cache};
+        HIP_TRY_K(st, FS_K_PREPARE, s,
+                  launch_tree_prepare(pl, max_depth, it.l_glo, it.seg_off, it.l_s, hd, st->at<double>(L.off_invf), st->at<uint64_t>(L.off_ancall),
+                                      anc + (size_t)row0 * FS_ANC_WORDS, rope + (size_t)row0 * (hd / 2), kr, s));
+        at.req[rq] = AttnReq{it.kv.base, row0, it.l_s, it.l_glo, it.l_cache + it.l_s};
+        row0 += it.l_s;
+        ++rq;
+    }
     int aMTW, aRB;
-    attn_plan(st->elem, hd, l_s, G, d.n_kv_heads, at.L, kMaxSplits, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
+    attn_plan(st->elem, hd, max_M, G, d.n_kv_heads * n_live, max_L, kMaxSplits, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
 
     // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
     // travel beside them as partial sums (see GemmArgs::gain_next)
-    // Segments of 128 rows and more (chunked prefill) take the MFMA-bound projection kernel; it uses the same hand-over of
-    // fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
+    // 128 rows and more (chunked prefill, batches of segments) take the MFMA-bound projection kernel; it uses the same
+    // hand-over of fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
+    const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
     const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
     const bool handover = w4 || wide;
@@ -504,18 +544,18 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
 
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerPlan& p = L.layers[l];
-        unsigned char* klayer = (unsigned char*)kv.base + (size_t)l * kv.stride_layer * st->elem;
+        const long long layer_off = (long long)l * kv0->stride_layer;
         const bool first = (l == 0), last = (l == d.n_layers - 1);
         // RMSNorm + QKV + RoPE + cache append
         GemmArgs g{};
         g.X = (first && !handover) ? hidden_in : hb; g.x_frag = (first && !handover) ? 0 : 1; g.ldx = d.d_model; g.M = l_s; g.K = p.qkv.K; g.nkt = p.qkv.nkt; g.N = p.qkv.N; g.Wp = p.qkv.wp;
-        g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.k_layer = klayer;
-        g.stride_kv = kv.stride_kv; g.stride_head = kv.stride_head; g.stride_tok = kv.stride_tok;
-        g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd; g.slot0 = l_cache;
+        g.eps = d.rms_eps; g.bias = p.qkv.bias; g.rope = rope; g.q_out = q; g.krow = krow; g.layer_off = layer_off;
+        g.stride_kv = kv0->stride_kv; g.stride_head = kv0->stride_head;
+        g.Hq = d.n_q_heads; g.Hkv = d.n_kv_heads; g.hd = hd;
         g.ssp_in = sspa; g.ssp_n = first ? ssp_n_first : res_parts; g.ssp_stride = L.ssp_stride;
         HIP_TRY_K(st, FS_K_QKV, s, launch_proj(st, EPI_QKV, p.qkv, g, s, wide));
         // tree attention
-        at.k_layer = klayer;
+        at.layer_off = layer_off;
         HIP_TRY_K(st, FS_K_ATTN, s, launch_attention(d.dtype, at, aMTW, aRB, s));
         // output projection + residual
         g = GemmArgs{};
@@ -541,6 +581,20 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
         HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s, wide));
     }
     return FS_OK;
+}
+
+int fs_tree_verify_batch(fs_stage* st, const fs_batch_item* items, int n_items, const void* hidden_in, void* hidden_out, void* stream) {
+    return verify_batch(st, items, n_items, hidden_in, hidden_out, stream);
+}
+
+int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const void* hidden_in, int seg_off, int l_s, const int32_t* parent,
+                         void* hidden_out, void* stream) {
+    if (!st || l_s < 0 || seg_off < 0 || l_glo < 0) return FS_EINVAL;
+    if (l_cache != l_glo + seg_off) return FS_EINVAL;
+    if (l_s == 0) return FS_OK;
+    if (!hidden_in || !hidden_out || !parent) return FS_EINVAL;
+    fs_batch_item it{kv, l_glo, l_cache, seg_off, l_s, parent};
+    return verify_batch(st, &it, 1, hidden_in, hidden_out, stream);
 }
 
 int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int32_t* amax, void* stream) {

@@ -30,7 +30,7 @@
 
 // Merge of the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, in split order.
 template <typename T>
-static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c) {
+static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c) {  // rho: stacked over the batch
     using E = Elem<T>;
     // one pass with a running maximum: every load is independent of the arithmetic, so they all go out together
     float m = NEG_BIG, den = 0.f;
@@ -49,13 +49,17 @@ static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kv
         m = mn;
     }
     const float inv = 1.0f / den;
-    const int qh = kvh * a.G + rho / a.M, r = rho % a.M;
+    // the request that owns this row: stacked rows [G * row0, G * (row0 + M))
+    int rq = 0;
+    while (rq + 1 < a.n_req && rho >= a.G * a.req[rq + 1].row0) ++rq;
+    const int M = a.req[rq].M, loc = rho - a.G * a.req[rq].row0;
+    const int qh = kvh * a.G + loc / M, r = a.req[rq].row0 + loc % M;
     *(typename E::out4_t*)((T*)a.o + frag_major_index<T>(r, qh * a.hd + c * 4, a.Hq * a.hd / E::KT)) =
         E::pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
 }
 
 template <typename T, int HD, int MTW>
-__global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const AttnArgs a) {
     using E = Elem<T>;
     using frag_t = typename E::frag_t;
     constexpr int EPF = E::EPF, KT = E::KT;
@@ -77,9 +81,16 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nthr = blockDim.x;
     const int r16 = lane & 15, g = lane >> 4;
-    const int split = blockIdx.x, kvh = blockIdx.y, rb = blockIdx.z;
-    const int R = a.G * a.M;
-    const int ntiles = (a.L + BS - 1) / BS;
+    // grid: (KV split, KV head, request x row block); row_blocks is a leading scalar argument so that the request's table
+    // entry can be fetched together with the other kernel arguments
+    const int split = blockIdx.x, kvh = blockIdx.y, rqi = blockIdx.z / row_blocks, rb = blockIdx.z % row_blocks;
+    const AttnReq rq = a.req[rqi];
+    const int M = rq.M, L = rq.L, l_glo = rq.l_glo, row0 = rq.row0;
+    const int R = a.G * M;
+    // a shorter request of the batch may have no such row block: the workgroup then walks no tiles and stores nothing
+    // (no early exit here: a branch on a freshly loaded kernel argument would hold back every other argument load)
+    const bool dead = rb * a.nwc * MTW * 16 >= R;
+    const int ntiles = dead ? 0 : (L + BS - 1) / BS;
     const int t0 = split * a.tiles_per_split, t1 = min(ntiles, t0 + a.tiles_per_split);
     // waves beyond the compute waves (or whose rows all lie beyond R) only help staging
     const bool computes = (w < a.nwc) && ((rb * a.nwc + w) * MTW * 16 < R);
@@ -92,8 +103,8 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         rho[i] = ((rb * a.nwc + w) * MTW + i) * 16 + r16;
         rok[i] = computes && rho[i] < R;
         const int rr = rok[i] ? rho[i] : 0;
-        seg_r[i] = rr % a.M;
-        const int qh = kvh * a.G + rr / a.M;
+        seg_r[i] = row0 + rr % M;  // row of the stacked arrays
+        const int qh = kvh * a.G + rr / M;
         const T* qp = (const T*)a.q + (size_t)seg_r[i] * (a.Hq * HD) + (size_t)qh * HD + g * EPF;
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) qf[i][kt] = rok[i] ? *(const frag_t*)(qp + kt * KT) : E::zero();
@@ -109,7 +120,7 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         for (int nt = 0; nt < NHT; ++nt) acc[i][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const T* kbase = (const T*)a.k_layer + (size_t)kvh * a.stride_head;
+    const T* kbase = (const T*)rq.kbase + a.layer_off + (size_t)kvh * a.stride_head;
     const T* vbase = kbase + a.stride_kv;
 
     // chunk c of a tile -> K: row-major (slot = c / NCC); V: lane -> (slot_lo, chunk part) so that the transposing
@@ -121,13 +132,13 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         for (int i = 0; i < CPT; ++i) {
             const int c = tid + i * nthr;
             if (c < CH) {
-                const int ks = min(s0 + c / NCC, a.L - 1);  // slots beyond L re-read the last valid one; they are masked below
+                const int ks = min(s0 + c / NCC, L - 1);  // slots beyond L re-read the last valid one; they are masked below
                 kreg[i] = *(const frag_t*)(kbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
                 if (VTR) {
                     vreg[i] = *(const frag_t*)(vbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
                 } else {
                     const int it = c >> 6, ln = c & 63;
-                    const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), a.L - 1);
+                    const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), L - 1);
                     vreg[i] = *(const frag_t*)(vbase + (size_t)vs * a.stride_tok + ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF);
                 }
             }
@@ -164,10 +175,10 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         // (slots below l_glo are always visible; draft slot l_glo + j by bit j of the row's ancestor mask; slots
         // beyond L never).  Tiles below l_glo need no mask; a wave none of whose rows sees any slot of the tile
         // skips it (deep chains: the upper triangle).
-        const bool need_mask = (s0 + BS > a.l_glo);  // tile touches draft slots or the tail beyond L
+        const bool need_mask = (s0 + BS > l_glo);  // tile touches draft slots or the tail beyond L
         uint64_t vm[MTW];
         if (need_mask) {
-            const int d0 = s0 - a.l_glo, valid = a.L - s0;  // valid >= 1
+            const int d0 = s0 - l_glo, valid = L - s0;  // valid >= 1
             bool any = false;
 #pragma unroll
             for (int i = 0; i < MTW; ++i) {
@@ -277,13 +288,13 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
         if (!rok[i]) continue;
         if (a.n_splits == 1) {
             const float inv = 1.0f / l;
-            const int qh = kvh * a.G + rho[i] / a.M;
+            const int qh = kvh * a.G + rho[i] / M;
 #pragma unroll
             for (int nt = 0; nt < NHT; ++nt)
                 *(typename E::out4_t*)((T*)a.o + frag_major_index<T>(seg_r[i], qh * HD + nt * 16 + g * 4, a.Hq * HD / KT)) =
                     E::pack4(acc[i][nt][0] * inv, acc[i][nt][1] * inv, acc[i][nt][2] * inv, acc[i][nt][3] * inv);
         } else {
-            const size_t prow = ((size_t)split * a.Hkv + kvh) * a.Rpad + rho[i];
+            const size_t prow = ((size_t)split * a.Hkv + kvh) * a.Rpad + a.G * row0 + rho[i];
             float* po = a.part_o + prow * HD + g * 4;
 #pragma unroll
             for (int nt = 0; nt < NHT; ++nt) *(f32x4*)(po + nt * 16) = acc[i][nt];
@@ -296,7 +307,7 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(const AttnArgs a) {
 // Combine the splits: one thread per (KV head, row, 4 head-dim elements).
 template <typename T>
 __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
-    const int R = a.G * a.M, hd4 = a.hd / 4;
+    const int R = a.G * a.rows, hd4 = a.hd / 4;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= a.Hkv * R * hd4) return;
     merge_row_chunk<T>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4);
@@ -305,14 +316,14 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 template <typename T, int HD>
 static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
     const int nw = a.nwc < 4 ? 4 : a.nwc;  // at least 256 threads share the staging of a tile
-    dim3 grid(a.n_splits, a.Hkv, row_blocks), block(nw * 64);
+    dim3 grid(a.n_splits, a.Hkv, row_blocks * a.n_req), block(nw * 64);
     if (MTW == 1)
-        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1>), grid, block, 0, s, row_blocks, a);
     else
-        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2>), grid, block, 0, s, row_blocks, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.n_splits > 1) {
-        const int total = a.Hkv * a.G * a.M * (a.hd / 4);
+        const int total = a.Hkv * a.G * a.rows * (a.hd / 4);
         hipLaunchKernelGGL(attn_merge_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, s, a);
         e = hipGetLastError();
     }

@@ -2,19 +2,30 @@
 #pragma once
 #include "common.hpp"
 
+constexpr int ATTN_MAX_REQ = 32;
+
+// One request of a batch: its rows [row0, row0 + M) of the stacked q / o / anc arrays, its cache and its lengths.
+struct AttnReq {
+    const void* kbase;  // K cache of the request (layer 0); V at + stride_kv
+    int row0, M;
+    int l_glo, L;       // L = l_cache + l_s: slots [0, L) take part
+};
+
 struct AttnArgs {
-    const void* q;        // [M][Hq*hd]
-    const void* k_layer;  // K cache of this layer; V at + stride_kv
+    const void* q;        // [rows][Hq*hd], rows of all requests stacked
+    long long layer_off;  // elements from a request's kbase to the layer's K cache
     long long stride_kv, stride_head, stride_tok;
-    void* o;              // [M][Hq*hd] in fragment-major layout (operand of the output projection)
-    int M, Hq, Hkv, hd, G;
-    int l_glo, L;         // L = l_cache + l_s: slots [0, L) take part
-    const uint64_t* anc;  // [M][FS_ANC_WORDS] ancestor-or-self masks of the segment rows (bit j = S index j)
+    void* o;              // [rows][Hq*hd] in fragment-major layout (operand of the output projection)
+    int Hq, Hkv, hd, G;
+    int n_req, rows;      // requests, stacked rows in total
+    int max_M, max_L;     // largest M and L of the batch (grid and split plan)
+    const uint64_t* anc;  // [rows][FS_ANC_WORDS] ancestor-or-self masks of the segment rows (bit j = S index j of the row's own tree)
     float scale_log2;     // log2(e) / sqrt(hd)
     int n_splits, tiles_per_split, Rpad;
-    float* part_o;        // [n_splits][Hkv][Rpad][hd]
+    float* part_o;        // [n_splits][Hkv][Rpad][hd], Rpad >= G * rows; row G * row0 + rho of a request
     float* part_ml;       // [n_splits][Hkv][Rpad][2]
     int nwc;              // compute waves per workgroup (workgroups have at least 4 waves for staging)
+    AttnReq req[ATTN_MAX_REQ];  // last: the fields above stay within the first cache lines of the kernel-argument segment
 };
 
 // slots per LDS tile for a given element size and head dim

@@ -120,12 +120,12 @@ static __device__ __forceinline__ float epilogue_item(const GemmArgs& a, const f
             if (head < a.Hq)
                 dst = (T*)a.q_out + (size_t)m * (a.Hq * a.hd) + (size_t)head * a.hd;
             else
-                dst = (T*)a.k_layer + (size_t)(head - a.Hq) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+                dst = (T*)a.krow[m] + a.layer_off + (size_t)(head - a.Hq) * a.stride_head;
             *(typename E::out4_t*)(dst + t) = E::pack4(olo[0], olo[1], olo[2], olo[3]);
             *(typename E::out4_t*)(dst + t + half) = E::pack4(ohi[0], ohi[1], ohi[2], ohi[3]);
         } else if (head < a.Hq + 2 * a.Hkv) {
             // v head: natural tile order, no rotation
-            T* dst = (T*)a.k_layer + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head + (size_t)(a.slot0 + m) * a.stride_tok;
+            T* dst = (T*)a.krow[m] + a.layer_off + a.stride_kv + (size_t)(head - a.Hq - a.Hkv) * a.stride_head;
             const int t = tih * 16 + g * 4;
             *(typename E::out4_t*)(dst + t) = E::pack4(lo[0], lo[1], lo[2], lo[3]);
             *(typename E::out4_t*)(dst + t + 16) = E::pack4(hi[0], hi[1], hi[2], hi[3]);

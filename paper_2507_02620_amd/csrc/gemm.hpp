@@ -31,9 +31,10 @@ struct GemmArgs {
     // EPI_QKV
     const float2* rope;  // [M][hd/2] (cos, sin)
     void* q_out;         // [M][Hq*hd]
-    void* k_layer;       // K cache of this layer (kv = 0), V at + stride_kv
-    long long stride_kv, stride_head, stride_tok;
-    int Hq, Hkv, hd, slot0;
+    const unsigned long long* krow;  // [M] address of the row's K cache slot (layer 0, head 0) in its request's cache
+    long long layer_off;             // elements from there to this layer's K cache; V at + stride_kv
+    long long stride_kv, stride_head;
+    int Hq, Hkv, hd;
     // EPI_RESID
     const void* resid;  // [M][N] fp32 residual stream, or T-typed stage input when resid_is_T
     int resid_is_T;

@@ -20,7 +20,8 @@ hipError_t launch_rope_freq(double* inv_freq, int hd, float theta, hipStream_t s
 
 __global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd,
                                                            const double* __restrict__ inv_freq, uint64_t* __restrict__ anc,
-                                                           float2* __restrict__ rope) {
+                                                           float2* __restrict__ rope, KRowArgs kr) {
+    for (int r = threadIdx.x; r < l_s; r += blockDim.x) kr.krow[r] = kr.base + (unsigned long long)(kr.slot0 + r) * kr.tok_bytes;
     __shared__ short par[1024];
     __shared__ int pos[1024];
     const int T = seg_off + l_s;
@@ -63,7 +64,8 @@ __global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent,
 // round relies on.  J and D are updated behind a barrier.
 __global__ void __launch_bounds__(1024) tree_prepare_deep_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd,
                                                                  const double* __restrict__ inv_freq, uint64_t* A,
-                                                                 uint64_t* __restrict__ anc, float2* __restrict__ rope) {
+                                                                 uint64_t* __restrict__ anc, float2* __restrict__ rope, KRowArgs kr) {
+    for (int r = threadIdx.x; r < l_s; r += blockDim.x) kr.krow[r] = kr.base + (unsigned long long)(kr.slot0 + r) * kr.tok_bytes;
     __shared__ short J[1024];
     __shared__ int D[1024];
     const int T = seg_off + l_s, i = threadIdx.x;
@@ -109,11 +111,11 @@ __global__ void __launch_bounds__(1024) tree_prepare_deep_kernel(const IdxList p
 }
 
 hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq,
-                               uint64_t* anc_all, uint64_t* anc, float2* rope, hipStream_t s) {
+                               uint64_t* anc_all, uint64_t* anc, float2* rope, const KRowArgs& kr, hipStream_t s) {
     if (max_depth > 32)
-        hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all, anc, rope);
+        hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all, anc, rope, kr);
     else
-        hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope);
+        hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope, kr);
     return hipGetLastError();
 }
 

@@ -18,10 +18,18 @@ struct CompactArgs {
 };
 
 hipError_t launch_rope_freq(double* inv_freq, int hd, float theta, hipStream_t s);
-// anc [l_s][FS_ANC_WORDS], rope [l_s][hd/2]; max_depth (of the tree, from the host's validation pass) picks the walking kernel
+// Where the segment's K/V rows go: krow[r] = base + (slot0 + r) * tok_bytes, the address of row r's K slot (layer 0, head 0).
+struct KRowArgs {
+    unsigned long long* krow;  // [l_s]
+    unsigned long long base;   // the request's cache
+    unsigned long long tok_bytes;
+    int slot0;                 // l_cache
+};
+
+// anc [l_s][FS_ANC_WORDS], rope [l_s][hd/2], kr.krow [l_s]; max_depth (of the tree, from the host's validation pass) picks the walking kernel
 // or, for deep trees, the pointer-doubling one, which needs anc_all [seg_off + l_s][FS_ANC_WORDS] as scratch.
 hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq,
-                               uint64_t* anc_all, uint64_t* anc, float2* rope, hipStream_t s);
+                               uint64_t* anc_all, uint64_t* anc, float2* rope, const KRowArgs& kr, hipStream_t s);
 hipError_t launch_argmax(const float* logits, int rows, int vocab, int chunks, int32_t* work, int32_t* amax, hipStream_t s);
 hipError_t launch_accept(const int32_t* amax, const int32_t* token, const int32_t* parent, int T, int n_ver, AcceptResultDev* res,
                          int32_t* retain, hipStream_t s);

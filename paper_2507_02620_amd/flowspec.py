@@ -24,7 +24,7 @@ _ERR = {FS_EINVAL: "FS_EINVAL", FS_ETOPO: "FS_ETOPO", FS_ECAP: "FS_ECAP", FS_EDT
 KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "argmax", "compact")
 
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
-           "fs_stage_profile_end", "fs_tree_verify_stage",
+           "fs_stage_profile_end", "fs_tree_verify_stage", "fs_tree_verify_batch",
            "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
            "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16")
 
@@ -57,6 +57,13 @@ class KVCache(C.Structure):
                 ("stride_tok", C.c_longlong)]
 
 
+class BatchItem(C.Structure):
+    _fields_ = [("kv", KVCache), ("l_glo", C.c_int), ("l_cache", C.c_int), ("seg_off", C.c_int), ("l_s", C.c_int), ("parent", C.POINTER(C.c_int32))]
+
+
+FS_MAX_BATCH = 32
+
+
 class AcceptResult(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_acc", "x_new", "n_new", "continuous", "n_retain", "n_pr_verified")]
 
@@ -76,6 +83,7 @@ def _load():
     lib.fs_stage_profile_begin.argtypes = [vp, ci]
     lib.fs_stage_profile_end.argtypes = [vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
     lib.fs_tree_verify_stage.argtypes = [vp, KVCache, ci, ci, vp, ci, ci, i32p, vp, vp]
+    lib.fs_tree_verify_batch.argtypes = [vp, C.POINTER(BatchItem), ci, vp, vp, vp]
     lib.fs_tree_logits.argtypes = [vp, vp, ci, vp, vp, vp]
     lib.fs_tree_accept.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, vp]
     lib.fs_tree_accept_sample.argtypes = [vp, ci, C.c_float, vp, vp, ci, ci, C.c_uint64, C.c_uint64, vp, vp, vp, vp]
@@ -191,6 +199,20 @@ class Stage:
         assert par.shape[0] >= seg_off + l_s
         _check(_lib.fs_tree_verify_stage(self._handle, kv_descriptor(kv), int(l_glo), int(l_cache), _dp(hidden_in), int(seg_off), l_s, pp,
                                          _dp(hidden_out), _stream(stream)), "fs_tree_verify_stage")
+        return hidden_out
+
+    def tree_verify_batch(self, items, hidden_in, hidden_out=None, stream=None):
+        """items: sequence of (kv tensor, l_glo, l_cache, seg_off, l_s, parent) — one segment per request; hidden_in holds the
+        items' rows stacked in item order."""
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        arr = (BatchItem * len(items))()
+        keep = []
+        for i, (kv, l_glo, l_cache, seg_off, l_s, parent) in enumerate(items):
+            par = np.ascontiguousarray(parent, dtype=np.int32)
+            keep.append(par)
+            arr[i] = BatchItem(kv_descriptor(kv), int(l_glo), int(l_cache), int(seg_off), int(l_s), par.ctypes.data_as(C.POINTER(C.c_int32)))
+        _check(_lib.fs_tree_verify_batch(self._handle, arr, len(items), _dp(hidden_in), _dp(hidden_out), _stream(stream)), "fs_tree_verify_batch")
         return hidden_out
 
     def tree_logits(self, hidden, logits=None, amax=None, stream=None):
