@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
     ap.add_argument("--no-probes", action="store_true", help="skip the achievable-peak probes (pure streaming read, pure MFMA loop) and the "
                     "large-size KV compaction measurement")
+    ap.add_argument("--batch", type=int, default=1, metavar="B",
+                    help="B > 1: B independent requests (own KV cache, tree and hidden states) served by the stage together through "
+                         "fs_tree_verify_batch; tokens/s counts all of them")
     ap.add_argument("--graph", action="store_true", help="capture one whole step into a HIP graph and time its replays")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run one plain device-to-device copy of this many MiB (a kernel of known "
@@ -87,6 +90,10 @@ def main():
     use_head = cfg.vocab > 0 and not args.no_head
 
     t_setup = time.time()
+    B = max(1, args.batch)
+    if B > 1 and (args.temperature > 0 or args.graph or B > fs.FS_MAX_BATCH or B * cfg.seg_len > 1024):
+        print("bench.py: --batch needs greedy acceptance, no --graph, B <= %d and B * segment <= 1024" % fs.FS_MAX_BATCH, file=sys.stderr)
+        sys.exit(2)
     w4 = args.weights == "int4"
     up = lambda a: None if a is None else torch.from_numpy(a).to(dev, tdt)
     if w4:
@@ -95,13 +102,13 @@ def main():
         codes = lambda a: None if a is None else torch.from_numpy(a).to(dev)
         dev_layers = [{k: (codes(v) if v is not None and v.dtype == np.uint8 else up(v)) for k, v in lw.items()} for lw in host_layers]
         dfn, dlm, dls = up(fn), codes(lm), up(lm_scale)
-        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm, lm_head_scale=dls, weight_format=fs.FS_WFMT_INT4_G128)
+        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm, lm_head_scale=dls, weight_format=fs.FS_WFMT_INT4_G128, max_seg=B * cfg.seg_len)
     else:
         host_layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.n_layers)]
         fn, lm = synth.head_weights(cfg, seed) if use_head else (None, None)
         dev_layers = [{k: up(v) for k, v in lw.items()} for lw in host_layers]
         dfn, dlm, dls = up(fn), up(lm), None
-        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm)
+        stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm, max_seg=B * cfg.seg_len)
     torch.cuda.synchronize()
     del dev_layers, dfn, dlm, dls
     torch.cuda.empty_cache()
@@ -127,7 +134,40 @@ def main():
     plant_toks = torch.tensor([t for _, t in plants], dtype=torch.long, device=dev)
     swork = torch.empty(32 + 12 * T, dtype=torch.uint8, device=dev)
     step_no = [0]
+    if B > 1:
+        # requests 1 .. B-1: same prefix contents (a copy of request 0's cache), own tree, hidden states and planted path
+        reqs = [dict(kv=kv, tree=tree, hid=hid, token=token_d, parent=parent_d, amax=amax, res=res, retain=retain, work=work,
+                     plant_rows=plant_rows, plant_toks=plant_toks)]
+        for r in range(1, B):
+            tr = synth.random_tree(cfg.tree_size, cfg.max_depth, cfg.max_branch, max(cfg.vocab, 2), seed, stream=r, forest=cfg.forest)
+            pl = synth.resolve_plants(synth.plant_path(tr, T, seed, r, p_stop=0.0, mean_extra=2.0), tr, max(cfg.vocab, 2))
+            rs_, rt_, wk_ = fs.new_accept_buffers(T, T, dev)
+            reqs.append(dict(kv=kv.clone(), tree=tr, hid=up(synth.hidden(cfg, T, r, seed)), token=torch.from_numpy(tr.token).to(dev),
+                             parent=torch.from_numpy(tr.parent).to(dev), amax=torch.zeros(T, dtype=torch.int32, device=dev),
+                             res=rs_, retain=rt_, work=wk_,
+                             plant_rows=torch.tensor([a_ for a_, _ in pl], dtype=torch.long, device=dev),
+                             plant_toks=torch.tensor([b_ for _, b_ in pl], dtype=torch.int32, device=dev)))
+        stack_in = [torch.cat([q["hid"][o:o + n] for q in reqs], dim=0).contiguous() for o, n in segs]
+        stack_out = [torch.empty_like(x) for x in stack_in]
+        stack_logits = torch.zeros((B * cfg.seg_len, max(cfg.vocab, 1)), dtype=torch.float32, device=dev) if use_head else None
+        stack_amax = torch.zeros(B * cfg.seg_len, dtype=torch.int32, device=dev)
     setup_s = time.time() - t_setup
+
+    def step_batch():
+        l_glo = cfg.l_glo
+        for i, (off, n) in enumerate(segs):
+            items = [(q["kv"], l_glo, l_glo + off, off, n, q["tree"].parent[: off + n]) for q in reqs]
+            stage.tree_verify_batch(items, stack_in[i], stack_out[i])
+            if use_head:
+                stage.tree_logits(stack_out[i], stack_logits[: B * n], stack_amax[: B * n])
+                for r, q in enumerate(reqs):
+                    q["amax"][off:off + n] = stack_amax[r * n:(r + 1) * n]
+        for q in reqs:
+            # planted acceptance, written into the argmax (the logits of a batch stay stacked per segment)
+            q["amax"][q["plant_rows"]] = q["plant_toks"].to(torch.int32)
+            fs.tree_accept(None, q["amax"], q["token"], q["parent"], T, q["res"], q["retain"], q["work"])
+            stage.kv_compact(q["kv"], l_glo, l_glo + T, q["retain"], res=q["res"], new_len=new_len)
+            fs.seg_prune(q["hid"][segs[-1][0]:], segs[-1][0], q["retain"], res=q["res"], seg_out=pr_out, l_s_out=pr_n)
 
     def step():
         l_glo = cfg.l_glo
@@ -155,7 +195,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    run = step
+    run = step_batch if B > 1 else step
     if args.graph:
         # every launch of the step (the library's kernels take the tree as kernel arguments, nothing is allocated or
         # cleared by memset) goes into one graph on a side stream; a replay is one step
@@ -188,12 +228,12 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    tok_s = T * args.steps / dt
+    tok_s = B * T * args.steps / dt
 
     # second pass of the same steps with the per-kernel event timers armed
-    stage.profile_begin(args.steps * (len(segs) * (5 + 6 * cfg.n_layers) + 4) + 16)
+    stage.profile_begin(args.steps * (len(segs) * (5 + B + 6 * cfg.n_layers) + 4 * B) + 16)
     for _ in range(args.steps):
-        step()
+        (step_batch if B > 1 else step)()
     prof = stage.profile_end()
     out_res, out_ret = fs.accept_result_to_host(res, retain, T)
 
@@ -207,11 +247,11 @@ def main():
     stage_weight_bytes = cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model + 2 * cfg.n_kv_heads * cfg.head_dim * cfg.d_model
                                          + 3 * cfg.d_ffn * cfg.d_model) * welem
     head_bytes = cfg.vocab * cfg.d_model * welem if use_head else 0
-    kv_bytes = cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * elem * sum(cfg.l_glo + o + n for o, n in segs)
+    kv_bytes = B * cfg.n_layers * 2 * cfg.n_kv_heads * cfg.head_dim * elem * sum(cfg.l_glo + o + n for o, n in segs)
     step_bytes = int(len(segs) * (stage_weight_bytes + head_bytes) + kv_bytes)
 
     # the metric's two companions: MFMA utilisation of the projections and HBM rate of the tree attention
-    gemm_flops = 2.0 * sum(n for _, n in segs) * cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model
+    gemm_flops = 2.0 * B * sum(n for _, n in segs) * cfg.n_layers * (2 * cfg.n_q_heads * cfg.head_dim * cfg.d_model
                                                                    + 2 * cfg.n_kv_heads * cfg.head_dim * cfg.d_model + 3 * cfg.d_ffn * cfg.d_model)
     gemm_ms = sum(prof[k][0] for k in ("qkv", "oproj", "gateup", "down")) / args.steps
     mfma_peak = 157.3 if cfg.dtype == "f32" else 2500.0          # TFLOP/s, dense
@@ -225,14 +265,15 @@ def main():
                 "frac": round(at_bytes / (at_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
     # many-row segments run the MFMA-bound projection kernel: the dominant kernel is then priced against the matrix peak
-    wide = cfg.dtype == "bf16" and not w4 and cfg.seg_len >= 128
+    rows_per_launch = B * min(cfg.seg_len, T)
+    wide = cfg.dtype == "bf16" and not w4 and rows_per_launch >= 128
     if wide:
-        gu_flops = 2.0 * min(cfg.seg_len, T) * 2 * cfg.d_ffn * cfg.d_model
+        gu_flops = 2.0 * rows_per_launch * 2 * cfg.d_ffn * cfg.d_model
         gu_tf = gu_flops / (gu_avg_ms * 1e-3) / 1e12 if gu_n else 0.0
-        roofline = {"kernel": "wide_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up, %d rows)" % min(cfg.seg_len, T), "bound": "mfma",
+        roofline = {"kernel": "wide_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up, %d rows)" % rows_per_launch, "bound": "mfma",
                     "achieved": round(gu_tf, 1), "peak": mfma_peak, "unit": "TFLOP/s", "frac": round(gu_tf / mfma_peak, 4),
                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_flops": gu_flops,
-                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower()))}
+                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower())) if B == 1 else None}
     else:
         roofline = {"kernel": "skinny_gemm%s_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)" % ("_w4" if w4 else ""), "bound": "hbm",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -284,9 +325,9 @@ def main():
     # the same kernel's average duration in the committed rocprofv3 kernel trace (tool timestamps, without the two event
     # records that bracket every launch of the live measurement and add about 2 us to it)
     prof_us = None
-    if wide and args.workload == "P2":
+    if wide and args.workload == "P2" and B == 1:
         prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "wide_gemm_p2_kernel_trace.txt"), "void wide_gemm_kernel<2, false, 8, 4, 4>")
-    elif not wide and not w4 and args.workload == "C2":
+    elif not wide and not w4 and args.workload == "C2" and B == 1:
         prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "bench_c2_kernel_trace.txt"), "void skinny_gemm_kernel<bool _Accum, int, E, 2, 2>")
     if prof_us:
         roofline["rocprof_avg_launch_us"] = prof_us
@@ -302,7 +343,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name + ("-w4a16" if w4 else ""), "weights": "int4 codes, bf16 scale per 128 columns" if w4 else cfg.dtype, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
+        "config": {"workload": cfg.name + ("-w4a16" if w4 else "") + ("-batch%d" % B if B > 1 else ""), "requests": B, "weights": "int4 codes, bf16 scale per 128 columns" if w4 else cfg.dtype, "stage": "last" if use_head else "intermediate", "n_layers": cfg.n_layers, "d_model": cfg.d_model,
                    "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv x {cfg.head_dim}", "d_ffn": cfg.d_ffn, "vocab": cfg.vocab if use_head else 0,
                    "kv_prefix": cfg.l_glo, "tree_nodes": T, "segment": cfg.seg_len, "segments_per_step": len(segs),
                    "step": "verify x%d + lm_head + accept + kv_compact + seg_prune" % len(segs),

@@ -546,7 +546,12 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
 struct WideShape {
     int bmt, wnt, waves;
 };
-static WideShape wide_shape(int, int) { return {8, 4, 4}; }
+// Up to a few row blocks there are too few 256-feature blocks to fill the chip: 128-feature blocks (2 tiles per wave) then.
+static int wide_narrow_rows() {
+    static const int v = [] { const char* e = getenv("FLOWSPEC_WIDE_NARROW_ROWS"); return e ? atoi(e) : 384; }();
+    return v;
+}
+static WideShape wide_shape(int, int M) { return M < wide_narrow_rows() ? WideShape{8, 2, 4} : WideShape{8, 4, 4}; }
 
 struct WideGrid {
     int n_cols, m_blocks, k_splits;
@@ -574,10 +579,9 @@ int wide_ssp_parts(int M, int n_tiles) {
     return (n_tiles + col_tiles - 1) / col_tiles * sh.waves;
 }
 
-size_t wide_partial_bytes(int max_rows) {
-    // slices * row tiles * feature tiles KiB, with slices * blocks <= 512: at most 512 blocks' worth of tiles
-    const WideShape sh = wide_shape(EPI_RESID, max_rows);
-    return (size_t)512 * sh.bmt * sh.waves * sh.wnt * 1024;
+size_t wide_partial_bytes(int) {
+    // slices * row tiles * feature tiles KiB, with slices * blocks <= 512: at most 512 blocks' worth of tiles (largest block shape)
+    return (size_t)512 * 8 * 4 * 4 * 1024;
 }
 
 template <int EPI, int BMT, int WNT, int WAVES>
@@ -601,11 +605,20 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
 
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
     if (!a.x_frag) return hipErrorInvalidValue;
+    const bool narrow = wide_shape(epi, a.M).wnt == 2;
     switch (epi) {
-        case EPI_QKV: return launch_wide_shape<EPI_QKV, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
-        case EPI_SWIGLU: return launch_wide_shape<EPI_SWIGLU, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
-        case EPI_RESID: return launch_wide_shape<EPI_RESID, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
-        case EPI_LOGITS: return launch_wide_shape<EPI_LOGITS, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_QKV:
+            return narrow ? launch_wide_shape<EPI_QKV, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
+                          : launch_wide_shape<EPI_QKV, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_SWIGLU:
+            return narrow ? launch_wide_shape<EPI_SWIGLU, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
+                          : launch_wide_shape<EPI_SWIGLU, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_RESID:
+            return narrow ? launch_wide_shape<EPI_RESID, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
+                          : launch_wide_shape<EPI_RESID, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
+        case EPI_LOGITS:
+            return narrow ? launch_wide_shape<EPI_LOGITS, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
+                          : launch_wide_shape<EPI_LOGITS, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
     }
     return hipErrorInvalidValue;
 }
