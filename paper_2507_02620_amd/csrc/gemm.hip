@@ -334,6 +334,7 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
     // group instead were slower as well (gate/up 54 -> 61 us).
     const int MT = a.M <= 16 ? 1 : (a.M <= 32 ? 2 : 4);
     if (MT == 4 && NW > 4) NW = 4;
+    if (MT * NT >= 8 && NW > 4) NW = 4;  // 8 tiles per workgroup: 4 waves keep a copy each in LDS without reduction rounds
 #define FS_EPI(e)                                                                      \
     if (epi == e) {                                                                    \
         if (dtype == 0) return launch_mt_nt<float, e>(MT, NT, NW, n_groups, a, s);     \
@@ -375,7 +376,12 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
     constexpr bool NORM = (EPI != EPI_RESID);
     constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
     constexpr int TPI = PAIR ? 2 : 1;
-    constexpr int PFW = BMT == 8 ? 5 : 8;  // k-tiles of weights in flight per wave
+    // Weight fragments are fetched PFW k-tiles ahead and activation pieces XD k-tiles ahead.  Loads retire in order, so
+    // waiting for an activation piece also waits for every weight fetch issued before it: XD, not PFW, is the latency
+    // budget of a weight fetch, and PFW > XD + 1 only adds loads in flight.  (With XD = 2 a k-tile took 0.7 us whenever
+    // the weights came from HBM — one row block — i.e. about a third of the memory latency.)
+    constexpr int PFW = (BMT == 8 && WNT == 4) ? 4 : 8;
+    constexpr int XD = (BMT == 8 && WNT == 4) ? 4 : 8;
     constexpr int XL = BMT / WAVES;        // 16-byte pieces of the activation stage per thread
     static_assert(BMT % WAVES == 0 && BMT % 4 == 0, "row tiles must split over the waves and over groups of 4");
     __shared__ __align__(16) unsigned char xs[2][BMT * 1024];
@@ -394,9 +400,16 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 
     if (NORM && t < BMT * 16) {
         const int m = min(mt0 * 16 + t, a.M - 1);
-        float ssum = 0.f;
-        for (int j = 0; j < a.ssp_n; ++j) ssum += a.ssp_in[(size_t)j * a.ssp_stride + m];
-        rs_s[t] = 1.0f / sqrtf(ssum / (float)a.K + a.eps);
+        // a few dozen partial sums per row (one per 256-feature block of the producer): independent loads, unrolled
+        float s0 = 0.f, s1 = 0.f;
+        int j = 0;
+#pragma unroll 4
+        for (; j + 1 < a.ssp_n; j += 2) {
+            s0 += a.ssp_in[(size_t)j * a.ssp_stride + m];
+            s1 += a.ssp_in[(size_t)(j + 1) * a.ssp_stride + m];
+        }
+        if (j < a.ssp_n) s0 += a.ssp_in[(size_t)j * a.ssp_stride + m];
+        rs_s[t] = 1.0f / sqrtf((s0 + s1) / (float)a.K + a.eps);
     }
 
     // this wave's weight tiles; tiles beyond the matrix re-read the last one (their results are never stored).
@@ -427,7 +440,7 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 #pragma unroll
         for (int nt = 0; nt < WNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    frag_t wq[PFW][WNT], xr[2][XL];
+    frag_t wq[PFW][WNT], xr[XD][XL];
     auto fetch_w = [&](int j, int) {
 #pragma unroll
         for (int nt = 0; nt < WNT; ++nt) wq[j][nt] = load_w<T>(wbase + woff[nt]);
@@ -446,17 +459,18 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 #pragma unroll
         for (int i = 0; i < XL; ++i) *(frag_t*)(xs[buf] + (size_t)(w + WAVES * i) * 1024 + (size_t)lane * 16) = xr[j][i];
     };
-    // Pipeline, k-tile kt: weights in wq[kt % PFW] (fetched PFW k-tiles ahead: the weight fetch is the longest latency in the
-    // loop), activations in LDS buffer kt & 1; xr[(kt + 1) & 1] holds k-tile kt + 1 and xr[kt & 1] k-tile kt + 2 when the
-    // iteration starts.  One barrier per k-tile: it publishes buffer kt & 1 (filled during k-tile kt - 1) and tells that
-    // nobody still reads the other buffer, which the refill at the end of the iteration overwrites.
+    // Pipeline, k-tile kt: weights in wq[kt % PFW], activations in LDS buffer kt & 1; xr[n % XD] carries k-tile n from
+    // memory to LDS (n = kt + 1 .. kt + XD are in registers or in flight when the iteration starts).  One barrier per
+    // k-tile: it publishes buffer kt & 1 (filled during k-tile kt - 1) and tells that nobody still reads the other buffer,
+    // which the refill at the end of the iteration overwrites.
 #pragma unroll
     for (int j = 0; j < PFW; ++j) fetch_w(j, j);
-    load_x(0, 0);
-    load_x(1, 1);
+#pragma unroll
+    for (int j = 0; j < XD; ++j) load_x(j, j);
     store_x(0, 0);
-    load_x(0, 2);
-    constexpr int U = (PFW % 2 == 0) ? PFW : 2 * PFW;  // unroll so that kt % PFW and kt & 1 are compile-time
+    load_x(0, XD);
+    constexpr int U = (PFW % XD == 0) ? PFW : ((XD % PFW == 0) ? XD : PFW * XD);  // kt % PFW, kt % XD and kt & 1 compile-time
+    static_assert(U % 2 == 0 && U % PFW == 0 && U % XD == 0, "unroll factor must cover both rings and the buffer parity");
     for (int kt0 = 0; kt0 < nkt; kt0 += U) {
 #pragma unroll
         for (int ju = 0; ju < U; ++ju) {
@@ -475,8 +489,8 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 #pragma unroll
                         for (int mt = 0; mt < 4; ++mt) acc[h * 4 + mt][nt] = E::mma(wq[j][nt], bf[mt], acc[h * 4 + mt][nt]);
                 }
-                store_x((ju + 1) & 1, (ju + 1) & 1);
-                load_x((ju + 1) & 1, kt + 3);
+                store_x((ju + 1) % XD, (ju + 1) & 1);
+                load_x((ju + 1) % XD, kt + 1 + XD);
                 fetch_w(j, kt + PFW);
             }
         }
@@ -495,6 +509,12 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
         return;
     }
     // ---- epilogue straight from the accumulators -------------------------------------------------------------
+    // (residual projections also leave one partial sum of squares per row and workgroup: the waves' shares meet in LDS,
+    //  where the activation stage is free once every wave has left the loop)
+    float* hs = (float*)xs[0];  // [WAVES][BMT * 16]
+    if constexpr (EPI == EPI_RESID) {
+        if (a.ssp_out) __syncthreads();
+    }
 #pragma unroll
     for (int mt = 0; mt < BMT; ++mt) {
         const int m = (mt0 + mt) * 16 + r16;
@@ -510,9 +530,21 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
             hsq += epilogue_item<T, EPI>(a, y, rs, m, pt0 + ntp * TPI, g);
         }
         if constexpr (EPI == EPI_RESID) {
-            if (a.ssp_out) {  // one partial sum per wave (its WNT tiles) and row
+            if (a.ssp_out) {
                 hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
-                if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)(col * WAVES + w) * a.ssp_stride + m] = hsq;
+                if (g == 0) hs[w * (BMT * 16) + mt * 16 + r16] = hsq;
+            }
+        }
+    }
+    if constexpr (EPI == EPI_RESID) {
+        if (a.ssp_out) {
+            __syncthreads();
+            if (t < BMT * 16) {
+                float sum = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) sum += hs[ww * (BMT * 16) + t];
+                const int m = mt0 * 16 + t;
+                if (m < a.ssp_stride) a.ssp_out[(size_t)col * a.ssp_stride + m] = sum;
             }
         }
     }
@@ -524,8 +556,10 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int nt_all, int wnt, int k_splits, const float* part) {
     const int lane = threadIdx.x & 63, r16 = lane & 15, g = lane >> 4;
     const int m_tiles = (a.M + 15) >> 4, groups = nt_all / wnt;
-    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (unit >= m_tiles * groups) return;
+    __shared__ float hs[4][16];
+    const int wv = threadIdx.x >> 6;
+    const int unit = blockIdx.x * 4 + wv;  // groups is a multiple of 4: the workgroup's 4 units are the 4 waves' shares of one block
+    if (unit >= m_tiles * groups) return;  // whole workgroup
     const int mt = unit / groups, grp = unit % groups;
     const int m = mt * 16 + r16;
     float hsq = 0.f;
@@ -538,7 +572,10 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
     }
     if (a.ssp_out) {
         hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
-        if (g == 0 && m < a.ssp_stride) a.ssp_out[(size_t)grp * a.ssp_stride + m] = hsq;
+        if (g == 0) hs[wv][r16] = hsq;
+        __syncthreads();
+        if (threadIdx.x < 16 && mt * 16 + (int)threadIdx.x < a.ssp_stride)
+            a.ssp_out[(size_t)(grp >> 2) * a.ssp_stride + mt * 16 + threadIdx.x] = hs[0][threadIdx.x] + hs[1][threadIdx.x] + hs[2][threadIdx.x] + hs[3][threadIdx.x];
     }
 }
 
@@ -573,10 +610,10 @@ static WideGrid wide_grid(const WideShape& sh, int epi, int M, int n_tiles, int 
     return g;
 }
 
-int wide_ssp_parts(int M, int n_tiles) {
+int wide_ssp_parts(int M, int n_tiles) {  // one per workgroup column of the residual projection
     const WideShape sh = wide_shape(EPI_RESID, M);
     const int col_tiles = sh.waves * sh.wnt;
-    return (n_tiles + col_tiles - 1) / col_tiles * sh.waves;
+    return (n_tiles + col_tiles - 1) / col_tiles;
 }
 
 size_t wide_partial_bytes(int) {
@@ -665,12 +702,22 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
     const f32x4 resid_first = prefetch_resid<T, MT, NT, EPI>(a, w, grp, row0, r16, g);
     f32x4 acc[MT][NT];
     float ss[MT];
+    constexpr int SSP_LOADS = 12;  // 8 waves x 4 lane groups x 12 = 384 partial sums: d_model up to 6144 without the tail loop
+    float sp[MT][SSP_LOADS];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         ss[mt] = 0.f;
-        if (NORM) {  // this lane's share of the row's partial sums of squares; the cross-wave reduction adds the shares up
+        if (NORM) {
+            // This lane's share of the row's partial sums of squares; the cross-wave reduction adds the shares up.  The
+            // loads go out together here (a loop of load-wait-add would put several memory round trips in front of the
+            // first weight fetch); they are added up after the K loop.
             const int m = min(row0 + mt * 16 + r16, a.M - 1);
-            for (int j = w * 4 + g; j < a.ssp_n; j += 4 * NW) ss[mt] += a.ssp_in[(size_t)j * a.ssp_stride + m];
+#pragma unroll
+            for (int i = 0; i < SSP_LOADS; ++i) {
+                const int j = w * 4 + g + i * 4 * NW;
+                sp[mt][i] = j < a.ssp_n ? a.ssp_in[(size_t)j * a.ssp_stride + m] : 0.f;
+            }
+            for (int j = w * 4 + g + SSP_LOADS * 4 * NW; j < a.ssp_n; j += 4 * NW) ss[mt] += a.ssp_in[(size_t)j * a.ssp_stride + m];  // very wide models
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -748,6 +795,12 @@ __global__ void __launch_bounds__(512) skinny_gemm_w4_kernel(const GemmArgs a) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) consume(s, (nrounds - 1) * PF + s);
 
+    if (NORM) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < SSP_LOADS; ++i) ss[mt] += sp[mt][i];
+    }
     reduce_and_store<T, MT, NT, EPI>(a, acc, ss, smem, lane, w, NW, grp, row0, resid_first);
 }
 
@@ -779,6 +832,7 @@ hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs&
     // the quarter-size weights mostly hits in L2
     const int MT = a.M <= 16 ? 1 : 2;
     if (NW > 8) NW = 8;
+    if (MT * NT >= 8 && NW > 4) NW = 4;  // as in the dense launcher
     if (epi == EPI_QKV) return launch_mt_nt_w4<EPI_QKV>(MT, NT, NW, n_groups, a, s);
     if (epi == EPI_RESID) return launch_mt_nt_w4<EPI_RESID>(MT, NT, NW, n_groups, a, s);
     if (epi == EPI_SWIGLU) return launch_mt_nt_w4<EPI_SWIGLU>(MT, NT, NW, n_groups, a, s);
