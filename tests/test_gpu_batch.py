@@ -8,14 +8,14 @@ from paper_2507_02620_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def _run_batch(cfg, specs, seed, head=False):
+def _run_batch(cfg, specs, seed, head=False, w4=False):
     """specs: list of (l_glo, tree_size, max_depth, max_branch, seg_off, l_s).  Every request gets its own cache, tree and
     context; segments before seg_off are verified one request at a time first (they fill the cache)."""
     import torch
     from oracle import oracle
     from paper_2507_02620_amd import flowspec as fs
     from tests.gpu_util import Pair, to_dev
-    pair = Pair(cfg, seed=seed, head=head)          # weights + one oracle stage (its cache is reloaded per request)
+    pair = Pair(cfg, seed=seed, head=head, w4=w4)   # weights + one oracle stage (its cache is reloaded per request)
     tdt = pair.tdtype
     items, hid_rows, want = [], [], []
     caches = []
@@ -23,7 +23,7 @@ def _run_batch(cfg, specs, seed, head=False):
         tree = synth.random_tree(T, depth, branch, 1000, seed, stream=10 + r)
         hid = synth.hidden(cfg, T, 20 + r, seed)
         kv = pair.gpu.new_kv_cache()
-        orc = oracle.Stage(cfg, pair.layers, None, None, cfg.kv_capacity)
+        orc = oracle.Stage(cfg, [oracle.dequant_layer(lw) for lw in pair.layers] if w4 else pair.layers, None, None, cfg.kv_capacity)
         for l in range(cfg.n_layers):
             pre = synth.prefix_kv(cfg, l, cfg.kv_capacity, seed + 100 * r)
             pre[:, :, l_glo:] = 0
@@ -69,6 +69,22 @@ def test_batch_matches_per_request_oracle(name, cfg, specs):
         g = kv[l][:, :, l_glo + seg_off:l_glo + seg_off + l_s].float().cpu().numpy()
         o = orc.kv[l][:, :, l_glo + seg_off:l_glo + seg_off + l_s]
         assert max_rel_err(g, o) < TOL[cfg.dtype]
+
+
+def test_batch_with_4bit_weights():
+    """The batch path with 4-bit group weights (gains applied by the producing epilogue, row blocks of the few-row kernel)."""
+    from tests.gpu_util import TOL, max_rel_err
+    cfg = synth.StageConfig("b-w4", "bf16", 2, 512, 4, 2, 128, 1408, 0, 120, 48, 80, 6, 3)
+    specs = [(60 + 20 * i, 48, 6, 3, 16, 16) for i in range(5)]       # 80 stacked rows
+    print(f"[case] batch w4: {len(specs)} requests, 80 stacked rows", flush=True)
+    got, want, caches, cfg = _run_batch(cfg, specs, seed=21, w4=True)
+    row = 0
+    for r, w in enumerate(want):
+        n = w.shape[0]
+        err = max_rel_err(got[row:row + n], w)
+        print(f"  request {r}: hidden max-rel-err {err:.3e}", flush=True)
+        assert err < TOL["bf16"]
+        row += n
 
 
 def test_batch_errors():
