@@ -24,7 +24,12 @@
 
 #include <stdlib.h>
 
+#ifndef PADK
 #define PADK 8   /* elements; keeps K rows 16-byte aligned and spreads LDS banks */
+#endif
+#ifndef PADVR
+#define PADVR 8  /* the same for V rows staged row-major (16-bit types) */
+#endif
 #define PADV 16
 #define NEG_BIG (-1.0e30f)
 
@@ -58,8 +63,8 @@ static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kv
         E::pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
 }
 
-template <typename T, int HD, int MTW>
-__global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const AttnArgs a) {
+template <typename T, int HD, int MTW, int NWAVES, int NSET, bool STREAM>
+__global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) tree_attn_kernel(int row_blocks, const AttnArgs a) {
     using E = Elem<T>;
     using frag_t = typename E::frag_t;
     constexpr int EPF = E::EPF, KT = E::KT;
@@ -71,15 +76,16 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const At
     // bf16: V is staged row-major like K and read back transposed with the LDS transpose load of gfx950;
     // f32 (no 32-bit transpose load exists): V is transposed while it is stored.
     constexpr bool VTR = (sizeof(T) == 2);
-    constexpr int KROW = HD + PADK, VROW = VTR ? (HD + PADK) : (BS + PADV);
+    constexpr int KROW = HD + PADK, VROW = VTR ? (HD + PADVR) : (BS + PADV);
     constexpr int NCC = HD / EPF;     // 16-byte chunks per K/V row
     constexpr int CH = BS * NCC;      // chunks per tile (K and V each)
-    constexpr int CPT = CH / 256;     // chunks per thread at the smallest workgroup (256 threads)
-    static_assert(CH % 256 == 0, "tile must split evenly over 256 threads");
+    constexpr int NTHR = NWAVES * 64; // every thread stages; waves beyond the compute waves do nothing else
+    constexpr int CPT = CH / NTHR;    // chunks per thread (K and V each)
+    static_assert(CH % NTHR == 0, "tile must split evenly over the workgroup");
     __shared__ __align__(16) T Ks[BS * KROW];
     __shared__ __align__(16) T Vt[VTR ? BS * VROW : HD * VROW];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nthr = blockDim.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     // grid: (KV split, KV head, request x row block); row_blocks is a leading scalar argument so that the request's table
     // entry can be fetched together with the other kernel arguments
@@ -125,51 +131,62 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const At
 
     // chunk c of a tile -> K: row-major (slot = c / NCC); V: lane -> (slot_lo, chunk part) so that the transposing
     // LDS stores of one instruction spread over the banks
-    frag_t kreg[CPT], vreg[CPT];
-    auto fetch = [&](int tile) {
-        const int s0 = tile * BS;
+    // NSET tiles in flight per workgroup, each in a register set of its own: 2 for long splits where the budget allows (one
+    // row tile per wave), so that a fetch has two tile periods to arrive; 1 otherwise (less code for the short kernels).
+    static_assert(NSET == 1 || MTW == 1, "two register sets only with one row tile per wave");
+    frag_t kregs[NSET][CPT], vregs[NSET][CPT];
+    // Byte offsets of chunk i of this thread relative to the head's K (or V) base: row part and column part apart, so that the
+    // slot of a fetch is clamped to L - 1 with one add and one min per chunk (slots beyond L re-read the last valid one;
+    // they are masked below).  No branch inside a fetch: the compiler then counts the loads in flight exactly.
+    const unsigned row_bytes = (unsigned)(a.stride_tok * sizeof(T));
+    const unsigned last_row = (unsigned)(L - 1) * row_bytes;
+    unsigned krow_off[CPT], kcol_off[CPT], vrow_off[CPT], vcol_off[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = tid + i * NTHR;
+        krow_off[i] = (unsigned)(c / NCC) * row_bytes;
+        kcol_off[i] = (unsigned)((c % NCC) * EPF * sizeof(T));
+        if (VTR) {
+            vrow_off[i] = krow_off[i];
+            vcol_off[i] = kcol_off[i];
+        } else {
+            const int it = c >> 6, ln = c & 63;
+            vrow_off[i] = (unsigned)((it / (NCC / 4)) * 16 + (ln & 15)) * row_bytes;
+            vcol_off[i] = (unsigned)(((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF * sizeof(T));
+        }
+    }
+    auto fetch = [&](int tile, frag_t (&kreg)[CPT], frag_t (&vreg)[CPT]) {
+        const unsigned t = (unsigned)(tile * BS) * row_bytes;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int c = tid + i * nthr;
-            if (c < CH) {
-                const int ks = min(s0 + c / NCC, L - 1);  // slots beyond L re-read the last valid one; they are masked below
-                kreg[i] = *(const frag_t*)(kbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
-                if (VTR) {
-                    vreg[i] = *(const frag_t*)(vbase + (size_t)ks * a.stride_tok + (c % NCC) * EPF);
-                } else {
-                    const int it = c >> 6, ln = c & 63;
-                    const int vs = min(s0 + (it / (NCC / 4)) * 16 + (ln & 15), L - 1);
-                    vreg[i] = *(const frag_t*)(vbase + (size_t)vs * a.stride_tok + ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF);
-                }
-            }
+            const frag_t* kp = (const frag_t*)((const char*)kbase + (min(krow_off[i] + t, last_row) + kcol_off[i]));
+            const frag_t* vp = (const frag_t*)((const char*)vbase + (min(vrow_off[i] + t, last_row) + vcol_off[i]));
+            // K/V that one workgroup per head and split reads once is streamed past the caches; with several row blocks
+            // the later ones find it in L2
+            kreg[i] = STREAM ? __builtin_nontemporal_load(kp) : *kp;
+            vreg[i] = STREAM ? __builtin_nontemporal_load(vp) : *vp;
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](const frag_t (&kreg)[CPT], const frag_t (&vreg)[CPT]) {
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
-            const int c = tid + i * nthr;
-            if (c < CH) {
-                *(frag_t*)(&Ks[(c / NCC) * KROW + (c % NCC) * EPF]) = kreg[i];
-                if (VTR) {
-                    *(frag_t*)(&Vt[(c / NCC) * VROW + (c % NCC) * EPF]) = vreg[i];
-                } else {
-                    const int it = c >> 6, ln = c & 63;
-                    const int slot = (it / (NCC / 4)) * 16 + (ln & 15), col = ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF;
+            const int c = tid + i * NTHR;
+            *(frag_t*)(&Ks[(c / NCC) * KROW + (c % NCC) * EPF]) = kreg[i];
+            if (VTR) {
+                *(frag_t*)(&Vt[(c / NCC) * VROW + (c % NCC) * EPF]) = vreg[i];
+            } else {
+                const int it = c >> 6, ln = c & 63;
+                const int slot = (it / (NCC / 4)) * 16 + (ln & 15), col = ((it % (NCC / 4)) * 4 + (ln >> 4)) * EPF;
 #pragma unroll
-                    for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = vreg[i][e];
-                }
+                for (int e = 0; e < EPF; ++e) Vt[(col + e) * VROW + slot] = vreg[i][e];
             }
         }
     };
 
-    if (t0 < t1) fetch(t0);
-    for (int tile = t0; tile < t1; ++tile) {
+    // one tile from the staged copy in LDS
+    auto process = [&](int tile) {
         const int s0 = tile * BS;
-        __syncthreads();  // previous tile fully consumed
-        stash();
-        if (tile + 1 < t1) fetch(tile + 1);  // in flight across the barrier and while this tile is computed
-        __syncthreads();
-        if (!computes) continue;
+        if (!computes) return;
 
         // ---- visibility of the tile's slots for this lane's rows: bit b <-> slot s0 + b --------------------------
         // (slots below l_glo are always visible; draft slot l_glo + j by bit j of the row's ancestor mask; slots
@@ -196,7 +213,7 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const At
                 vm[i] = m >> (g * 4);
                 any |= (m != 0);
             }
-            if (__ballot(any) == 0) continue;  // wave-uniform; the staging above is already done
+            if (__ballot(any) == 0) return;  // wave-uniform; the staging is already done
         }
 
         // ---- S^T = K . Q^T ----
@@ -214,42 +231,64 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const At
         }
 
         // ---- mask, online softmax ----
+        // Tiles below l_glo (almost all of a long context) take the short form: no visibility test, scale folded into the
+        // exponent's multiply-add.  The running sums are rescaled only when some row's maximum moved (wave-uniform test).
         frag_t pf[MTW][NPF];
 #pragma unroll
         for (int i = 0; i < MTW; ++i) {
             float mx = NEG_BIG;
+            if (need_mask) {
 #pragma unroll
-            for (int j = 0; j < BS / 16; ++j)
+                for (int j = 0; j < BS / 16; ++j)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float s = st[i][j][v] * a.scale_log2;
-                    if (need_mask) {
+                    for (int v = 0; v < 4; ++v) {
+                        float s = st[i][j][v] * a.scale_log2;
                         const unsigned half = (j * 16 + v) < 32 ? (unsigned)vm[i] : (unsigned)(vm[i] >> 32);
                         if (!(half & (1u << ((j * 16 + v) & 31)))) s = NEG_BIG;
+                        st[i][j][v] = s;
+                        mx = fmaxf(mx, s);
                     }
-                    st[i][j][v] = s;
-                    mx = fmaxf(mx, s);
-                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < BS / 16; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) mx = fmaxf(mx, st[i][j][v]);
+                mx *= a.scale_log2;  // the scale is positive: the maximum commutes with it
+            }
             mx = wave_xor_max(wave_xor_max(mx, 16), 32);
             const float mnew = fmaxf(mrun[i], mx);
-            const float alpha = __builtin_amdgcn_exp2f(mrun[i] - mnew);  // arguments <= 0: the raw instruction is exact enough, underflow -> 0
-            mrun[i] = mnew;
+            if (__ballot(mnew != mrun[i]) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f(mrun[i] - mnew);  // arguments <= 0: the raw instruction is exact enough, underflow -> 0
+                lrun[i] *= alpha;
+#pragma unroll
+                for (int nt = 0; nt < NHT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[i][nt][v] *= alpha;
+                mrun[i] = mnew;
+            }
             float psum = 0.f;
             float p[BS / 16][4];
+            if (need_mask) {
 #pragma unroll
-            for (int j = 0; j < BS / 16; ++j)
+                for (int j = 0; j < BS / 16; ++j)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float s = st[i][j][v];
-                    const float e = (s <= NEG_BIG) ? 0.f : __builtin_amdgcn_exp2f(s - mnew);
-                    p[j][v] = e;
-                    psum += e;
-                }
-            lrun[i] = lrun[i] * alpha + psum;
+                    for (int v = 0; v < 4; ++v) {
+                        const float s = st[i][j][v];
+                        const float e = (s <= NEG_BIG) ? 0.f : __builtin_amdgcn_exp2f(s - mnew);
+                        p[j][v] = e;
+                        psum += e;
+                    }
+            } else {
 #pragma unroll
-            for (int nt = 0; nt < NHT; ++nt)
+                for (int j = 0; j < BS / 16; ++j)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[i][nt][v] *= alpha;
+                    for (int v = 0; v < 4; ++v) {
+                        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[i][j][v], a.scale_log2, -mnew));
+                        p[j][v] = e;
+                        psum += e;
+                    }
+            }
+            lrun[i] += psum;
 #pragma unroll
             for (int jj = 0; jj < NPF; ++jj)
 #pragma unroll
@@ -279,6 +318,40 @@ __global__ void __launch_bounds__(512) tree_attn_kernel(int row_blocks, const At
 #pragma unroll
                 for (int i = 0; i < MTW; ++i) acc[i][nt] = E::mma(vf, pf[i][jj], acc[i][nt]);
             }
+    };
+
+#pragma unroll
+    for (int k = 0; k < NSET; ++k)
+        if (t0 + k < t1) fetch(t0 + k, kregs[k], vregs[k]);
+    // Wait here for every load issued so far (Q fragments, first tiles): inside the loop the only vector-memory loads left to
+    // wait for are then tile fetches.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+    // Steady state: every tile of the group has a successor NSET tiles ahead, so store-and-refill is straight-line code
+    // and the wait before a store counts exactly the loads of the other register set that may stay in flight (a
+    // conditional refill would make the compiler wait for all of them, and the compute phase would never overlap a fetch).
+    int tile = t0;
+    for (; tile + 2 * NSET <= t1; tile += NSET) {
+#pragma unroll
+        for (int k = 0; k < NSET; ++k) {
+            __syncthreads();  // previous tile fully consumed
+            stash(kregs[k], vregs[k]);
+            fetch(tile + k + NSET, kregs[k], vregs[k]);  // in flight across the barriers and the next NSET tiles
+            __syncthreads();
+            process(tile + k);
+        }
+    }
+    // Tail: the last tiles (fewer than 2 * NSET), refilled only while a successor exists.
+    for (; tile < t1; tile += NSET) {
+#pragma unroll
+        for (int k = 0; k < NSET; ++k) {
+            if (tile + k < t1) {  // uniform over the workgroup
+                __syncthreads();
+                stash(kregs[k], vregs[k]);
+                if (tile + k + NSET < t1) fetch(tile + k + NSET, kregs[k], vregs[k]);
+                __syncthreads();
+                process(tile + k);
+            }
+        }
     }
 
     // ---- write out ----
@@ -315,12 +388,23 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 
 template <typename T, int HD>
 static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
-    const int nw = a.nwc < 4 ? 4 : a.nwc;  // at least 256 threads share the staging of a tile
+    const int nw = a.nwc <= 4 ? 4 : 8;  // every wave stages the tiles; the first a.nwc also compute
     dim3 grid(a.n_splits, a.Hkv, row_blocks * a.n_req), block(nw * 64);
-    if (MTW == 1)
-        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1>), grid, block, 0, s, row_blocks, a);
+    const bool deep = MTW == 1 && a.tiles_per_split >= 4;  // two tiles in flight pay from about 4 tiles per workgroup on
+    if (MTW == 1 && nw == 4 && deep)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 2, true>), grid, block, 0, s, row_blocks, a);
+    else if (MTW == 1 && nw == 4)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 1, true>), grid, block, 0, s, row_blocks, a);
+    else if (MTW == 1 && deep)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 2, true>), grid, block, 0, s, row_blocks, a);
+    else if (MTW == 1)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 1, true>), grid, block, 0, s, row_blocks, a);
+    else if (nw == 4)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 4, 1, true>), grid, block, 0, s, row_blocks, a);
+    else if (row_blocks == 1)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 8, 1, true>), grid, block, 0, s, row_blocks, a);
     else
-        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2>), grid, block, 0, s, row_blocks, a);
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 8, 1, false>), grid, block, 0, s, row_blocks, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.n_splits > 1) {
         const int total = a.Hkv * a.G * a.rows * (a.hd / 4);
@@ -333,10 +417,11 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
                int* tiles_per_split) {
     const int R = G * M, mtiles = (R + 15) / 16;
-    // up to 8 compute waves per workgroup, each with 1 or 2 row tiles
-    int nw = mtiles < 8 ? mtiles : 8;
-    int mtw = (mtiles + nw - 1) / nw > 1 ? 2 : 1;
-    nw = (mtiles + mtw - 1) / mtw;
+    // up to 8 compute waves per workgroup; from 4 row tiles on every wave takes 2 of them (each K/V fragment read from LDS
+    // then serves 32 rows)
+    int mtw = mtiles >= 4 ? 2 : 1;
+    if (const char* e = getenv("FLOWSPEC_ATTN_MTW")) mtw = (atoi(e) >= 2 && mtiles > 1) ? 2 : 1;
+    int nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
     *NWC = nw;
     *MTW = mtw;
