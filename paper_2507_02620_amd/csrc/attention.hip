@@ -33,18 +33,20 @@
 #define PADV 16
 #define NEG_BIG (-1.0e30f)
 
-// Merge of the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, in split order.
+// Merge of the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s.  MERGE_LANES adjacent
+// lanes share one output chunk: lane q takes splits q, q + MERGE_LANES, ... (all its loads are independent of the arithmetic
+// and go out together), then the lanes combine pairwise in a fixed order (deterministic).
+constexpr int MERGE_LANES = 4;
 template <typename T>
-static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c) {  // rho: stacked over the batch
+static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c, int q) {  // rho: stacked over the batch
     using E = Elem<T>;
-    // one pass with a running maximum: every load is independent of the arithmetic, so they all go out together
     float m = NEG_BIG, den = 0.f;
     f32x4 o{0.f, 0.f, 0.f, 0.f};
     const size_t sstride = (size_t)a.Hkv * a.Rpad;  // rows between consecutive splits
     const float* pml = a.part_ml + ((size_t)kvh * a.Rpad + rho) * 2;
     const float* po = a.part_o + ((size_t)kvh * a.Rpad + rho) * a.hd + c * 4;
-#pragma unroll 8
-    for (int s = 0; s < a.n_splits; ++s) {
+#pragma unroll 4
+    for (int s = q; s < a.n_splits; s += MERGE_LANES) {
         const float2 ml = *(const float2*)(pml + (size_t)s * sstride * 2);
         const f32x4 v = *(const f32x4*)(po + (size_t)s * sstride * a.hd);
         const float mn = fmaxf(m, ml.x);
@@ -53,6 +55,21 @@ static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kv
         o = o * w_old + v * w_new;
         m = mn;
     }
+#pragma unroll
+    for (int x = 1; x < MERGE_LANES; x <<= 1) {
+        const float m2 = __shfl_xor(m, x, FS_WAVE), den2 = __shfl_xor(den, x, FS_WAVE);
+        f32x4 o2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o2[e] = __shfl_xor(o[e], x, FS_WAVE);
+        const float mn = fmaxf(m, m2);
+        const float w1 = exp2f(m - mn), w2 = exp2f(m2 - mn);
+        // both lanes of a pair add in the same order (lower lane's term first), so they hold identical results
+        const bool lo = (q & x) == 0;
+        den = lo ? den * w1 + den2 * w2 : den2 * w2 + den * w1;
+        o = lo ? o * w1 + o2 * w2 : o2 * w2 + o * w1;
+        m = mn;
+    }
+    if (q != 0) return;
     const float inv = 1.0f / den;
     // the request that owns this row: stacked rows [G * row0, G * (row0 + M))
     int rq = 0;
@@ -377,13 +394,14 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
 }
 
 
-// Combine the splits: one thread per (KV head, row, 4 head-dim elements).
+// Combine the splits: MERGE_LANES threads per (KV head, row, 4 head-dim elements).
 template <typename T>
 __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     const int R = a.G * a.rows, hd4 = a.hd / 4;
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= a.Hkv * R * hd4) return;
-    merge_row_chunk<T>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4);
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int idx = t / MERGE_LANES, q = t % MERGE_LANES;
+    if (idx >= a.Hkv * R * hd4) return;  // whole groups of MERGE_LANES lanes leave together
+    merge_row_chunk<T>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4, q);
 }
 
 template <typename T, int HD>
@@ -407,7 +425,7 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 8, 1, false>), grid, block, 0, s, row_blocks, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.n_splits > 1) {
-        const int total = a.Hkv * a.G * a.rows * (a.hd / 4);
+        const int total = a.Hkv * a.G * a.rows * (a.hd / 4) * MERGE_LANES;
         hipLaunchKernelGGL(attn_merge_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, s, a);
         e = hipGetLastError();
     }
