@@ -447,7 +447,9 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     const int BS = attn_tile_slots(elem_bytes, hd);
     const int ntiles = (L + BS - 1) / BS;
     const char* env = getenv("FLOWSPEC_ATTN_WGS");
-    const int target = env ? atoi(env) : 512;  // about 2 workgroups per CU: measured best (C2: 256-512, C5: 512)
+    // about 2 workgroups per CU for long contexts (C5: 512 best, 384 and 768 +12 %); short ones are latency-bound and
+    // do slightly better with fewer, longer splits (C2: 256)
+    const int target = env ? atoi(env) : (ntiles <= 32 ? 256 : 512);
     int want = (target + Hkv * *row_blocks - 1) / (Hkv * *row_blocks);
     if (want > max_splits) want = max_splits;
     if (want > ntiles) want = ntiles;
