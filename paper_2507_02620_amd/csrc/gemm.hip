@@ -471,30 +471,35 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
     load_x(0, XD);
     constexpr int U = (PFW % XD == 0) ? PFW : ((XD % PFW == 0) ? XD : PFW * XD);  // kt % PFW, kt % XD and kt & 1 compile-time
     static_assert(U % 2 == 0 && U % PFW == 0 && U % XD == 0, "unroll factor must cover both rings and the buffer parity");
-    for (int kt0 = 0; kt0 < nkt; kt0 += U) {
+    auto ktile = [&](int ju) {  // k-tile kt0 + ju of a group of U: ring slots and buffer parity are compile-time
+        const int j = ju % PFW;
+        __syncthreads();
+        const unsigned char* xb = xs[ju & 1] + (size_t)lane * 16;
 #pragma unroll
-        for (int ju = 0; ju < U; ++ju) {
-            const int kt = kt0 + ju;
-            const int j = ju % PFW;
-            if (kt < nkt) {  // uniform over the workgroup
-                __syncthreads();
-                const unsigned char* xb = xs[ju & 1] + (size_t)lane * 16;
+        for (int h = 0; h < BMT / 4; ++h) {
+            frag_t bf[4];
 #pragma unroll
-                for (int h = 0; h < BMT / 4; ++h) {
-                    frag_t bf[4];
+            for (int mt = 0; mt < 4; ++mt) bf[mt] = *(const frag_t*)(xb + (size_t)(h * 4 + mt) * 1024);
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) bf[mt] = *(const frag_t*)(xb + (size_t)(h * 4 + mt) * 1024);
+            for (int nt = 0; nt < WNT; ++nt)
 #pragma unroll
-                    for (int nt = 0; nt < WNT; ++nt)
-#pragma unroll
-                        for (int mt = 0; mt < 4; ++mt) acc[h * 4 + mt][nt] = E::mma(wq[j][nt], bf[mt], acc[h * 4 + mt][nt]);
-                }
-                store_x((ju + 1) % XD, (ju + 1) & 1);
-                load_x((ju + 1) % XD, kt + 1 + XD);
-                fetch_w(j, kt + PFW);
-            }
+                for (int mt = 0; mt < 4; ++mt) acc[h * 4 + mt][nt] = E::mma(wq[j][nt], bf[mt], acc[h * 4 + mt][nt]);
         }
+        store_x((ju + 1) % XD, (ju + 1) & 1);
+        load_x((ju + 1) % XD, 0);
+        fetch_w(j, 0);
+    };
+    // Whole groups of U k-tiles run as straight-line code: a k-tile that could be skipped inside the loop would make the
+    // compiler assume that the fetch it is about to wait for might be the newest one in flight, and wait for all of them
+    // (the weight ring would then drain once per group).  The last, partial group takes the guarded form.
+    int kt0 = 0;
+    for (; kt0 + U <= nkt; kt0 += U) {
+#pragma unroll
+        for (int ju = 0; ju < U; ++ju) ktile(ju);
     }
+#pragma unroll
+    for (int ju = 0; ju < U; ++ju)
+        if (kt0 + ju < nkt) ktile(ju);  // uniform over the workgroup
 
     if constexpr (PARTIAL) {
         // raw tiles: part[ks][m tile][n tile][lane] (f32x4); tiles beyond the matrix are dropped
