@@ -593,13 +593,16 @@ static int wide_narrow_rows() {
     static const int v = [] { const char* e = getenv("FLOWSPEC_WIDE_NARROW_ROWS"); return e ? atoi(e) : 384; }();
     return v;
 }
+static int env_int(const char* name, int dflt) { const char* e = getenv(name); return e ? atoi(e) : dflt; }
 static WideShape wide_shape(int, int M) { return M < wide_narrow_rows() ? WideShape{8, 2, 4} : WideShape{8, 4, 4}; }
 
 struct WideGrid {
     int n_cols, m_blocks, k_splits;
 };
-// K slices for the d_model-wide residual projections: until there are about two workgroups per compute unit, at least 8
-// k-tiles per slice, and no more than the scratch array holds.
+// K slices for the d_model-wide residual projections: until there is about one workgroup per compute unit (measured: at 512
+// rows 4 slices -> 256 workgroups take 36 / 60 us for the attention-output / down projection, 8 slices 52 / 80 us; every
+// further slice adds a full set of partial tiles to write and to sum), at least 8 k-tiles per slice, and no more than the
+// scratch array holds.
 static WideGrid wide_grid(const WideShape& sh, int epi, int M, int n_tiles, int nkt, size_t part_bytes) {
     WideGrid g;
     const int col_tiles = sh.waves * sh.wnt;
@@ -608,7 +611,8 @@ static WideGrid wide_grid(const WideShape& sh, int epi, int M, int n_tiles, int 
     g.k_splits = 1;
     if (epi == EPI_RESID) {
         const size_t per_split = (size_t)((M + 15) / 16) * g.n_cols * col_tiles * 1024;
-        while (g.k_splits < 8 && g.n_cols * g.m_blocks * g.k_splits * 2 <= 512 && nkt / (g.k_splits * 2) >= 8 &&
+        static const int target = env_int("FLOWSPEC_WIDE_SPLIT_WGS", 256);
+        while (g.k_splits < 8 && g.n_cols * g.m_blocks * g.k_splits * 2 <= target && nkt / (g.k_splits * 2) >= 8 &&
                per_split * g.k_splits * 2 <= part_bytes)
             g.k_splits *= 2;
     }
