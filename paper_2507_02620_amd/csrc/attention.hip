@@ -35,9 +35,9 @@
 
 // Merge of the splits of one (KV head, row): out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s.  MERGE_LANES adjacent
 // lanes share one output chunk: lane q takes splits q, q + MERGE_LANES, ... (all its loads are independent of the arithmetic
-// and go out together), then the lanes combine pairwise in a fixed order (deterministic).
-constexpr int MERGE_LANES = 4;
-template <typename T>
+// and go out together), then the lanes combine pairwise in a fixed order (deterministic).  4 lanes from 4 splits on (few
+// rows, many splits: the kernel is latency-bound and wants its loads spread), 1 lane below (many rows, 2-3 splits).
+template <typename T, int MERGE_LANES>
 static __device__ __forceinline__ void merge_row_chunk(const AttnArgs& a, int kvh, int rho, int c, int q) {  // rho: stacked over the batch
     using E = Elem<T>;
     float m = NEG_BIG, den = 0.f;
@@ -395,13 +395,13 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
 
 
 // Combine the splits: MERGE_LANES threads per (KV head, row, 4 head-dim elements).
-template <typename T>
+template <typename T, int MERGE_LANES>
 __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     const int R = a.G * a.rows, hd4 = a.hd / 4;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     const int idx = t / MERGE_LANES, q = t % MERGE_LANES;
     if (idx >= a.Hkv * R * hd4) return;  // whole groups of MERGE_LANES lanes leave together
-    merge_row_chunk<T>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4, q);
+    merge_row_chunk<T, MERGE_LANES>(a, idx / (hd4 * R), (idx / hd4) % R, idx % hd4, q);
 }
 
 template <typename T, int HD>
@@ -425,8 +425,11 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 8, 1, false>), grid, block, 0, s, row_blocks, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.n_splits > 1) {
-        const int total = a.Hkv * a.G * a.rows * (a.hd / 4) * MERGE_LANES;
-        hipLaunchKernelGGL(attn_merge_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, s, a);
+        const int chunks = a.Hkv * a.G * a.rows * (a.hd / 4);
+        if (a.n_splits >= 4)
+            hipLaunchKernelGGL((attn_merge_kernel<T, 4>), dim3((chunks * 4 + 255) / 256), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_merge_kernel<T, 1>), dim3((chunks + 255) / 256), dim3(256), 0, s, a);
         e = hipGetLastError();
     }
     return e;
