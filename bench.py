@@ -326,7 +326,7 @@ def main():
     # records that bracket every launch of the live measurement and add about 2 us to it)
     prof_us = None
     if wide and args.workload == "P2" and B == 1:
-        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "wide_gemm_p2_kernel_trace.txt"), "void wide_gemm_kernel<2, false, 8, 4, 4>")
+        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "wide_gemm_p2_kernel_trace.txt"), "void wide_gemm_kernel<2, false, 8, 4, 4, false>")
     elif not wide and not w4 and args.workload == "C2" and B == 1:
         prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "bench_c2_kernel_trace.txt"), "void skinny_gemm_kernel<bool _Accum, int, E, 2, 2>")
     if prof_us:

@@ -367,7 +367,7 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
 //   * The block shape is a template parameter.  64-row blocks with 2 waves x 2 tiles per workgroup were tried for segments of
 //     33 to 127 rows and lost to the few-row kernel (64 rows: QKV 37 -> 75 us, gate/up 49 -> 91 us): a wave then has only 8
 //     MFMAs per k-tile to hide a barrier and an LDS round trip behind.
-template <int EPI, bool PARTIAL, int BMT, int WNT, int WAVES>
+template <int EPI, bool PARTIAL, int BMT, int WNT, int WAVES, bool STREAMW>
 __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
                                                            float* part) {
     using T = bf16_t;
@@ -443,7 +443,8 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
     frag_t wq[PFW][WNT], xr[XD][XL];
     auto fetch_w = [&](int j, int) {
 #pragma unroll
-        for (int nt = 0; nt < WNT; ++nt) wq[j][nt] = load_w<T>(wbase + woff[nt]);
+        for (int nt = 0; nt < WNT; ++nt)  // weights that other row blocks read again stay in L2; with one row block they stream past it
+            wq[j][nt] = STREAMW ? load_w<T>(wbase + woff[nt]) : *(const frag_t*)(wbase + woff[nt]);
         const unsigned adv = (++wk < nkt) ? wstep : 0u;  // past the slice's end the last k-tile is re-read (and never used)
 #pragma unroll
         for (int nt = 0; nt < WNT; ++nt) woff[nt] += adv;
@@ -635,17 +636,27 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
     const WideShape sh{BMT, WNT, WAVES};
     const WideGrid g = wide_grid(sh, EPI, a.M, n_tiles, a.nkt, part ? part_bytes : 0);
     const int grid = (g.n_cols + 7) / 8 * 8 * g.m_blocks * g.k_splits;
+    // one row block (only the narrow shape has that few rows): every weight byte is read once
+    const bool stream = (WNT == 2) && g.m_blocks == 1;
     if constexpr (EPI == EPI_RESID) {
         if (g.k_splits > 1) {
-            hipLaunchKernelGGL((wide_gemm_kernel<EPI, true, BMT, WNT, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
-                               g.m_blocks, g.k_splits, part);
+            if (stream)
+                hipLaunchKernelGGL((wide_gemm_kernel<EPI, true, BMT, WNT, WAVES, WNT == 2>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles,
+                                   g.n_cols, g.m_blocks, g.k_splits, part);
+            else
+                hipLaunchKernelGGL((wide_gemm_kernel<EPI, true, BMT, WNT, WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles,
+                                   g.n_cols, g.m_blocks, g.k_splits, part);
             const int units = ((a.M + 15) / 16) * g.n_cols * WAVES;
             hipLaunchKernelGGL(wide_fixup_kernel, dim3((units + 3) / 4), dim3(256), 0, s, a, g.n_cols * WAVES * WNT, WNT, g.k_splits, part);
             return hipGetLastError();
         }
     }
-    hipLaunchKernelGGL((wide_gemm_kernel<EPI, false, BMT, WNT, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
-                       g.m_blocks, 1, nullptr);
+    if (stream)
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI, false, BMT, WNT, WAVES, WNT == 2>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
+                           g.m_blocks, 1, nullptr);
+    else
+        hipLaunchKernelGGL((wide_gemm_kernel<EPI, false, BMT, WNT, WAVES, false>), dim3(grid), dim3(WAVES * 64), 0, s, a, layout_nt, n_tiles, g.n_cols,
+                           g.m_blocks, 1, nullptr);
     return hipGetLastError();
 }
 
