@@ -64,3 +64,20 @@ SMALL_BF16 = synth.StageConfig("small-bf16", "bf16", 2, 512, 4, 4, 128, 1376, 20
 ])
 def test_small_stages(name, cfg, seg):
     _check_stage(cfg.with_(name=name, seg_len=seg), 2, seg)
+
+
+@pytest.mark.parametrize("name,cfg,seg,wgs", [
+    # few workgroups -> long KV splits: the attention kernels that keep two tiles in flight, with even and odd tile counts and
+    # tails of 1 .. 3 tiles (l_glo + tree size spans 7, 10 and 13 tiles of 64 slots; 19 tiles of 32 slots for f32 / hd 128)
+    ("deep-7-tiles", SMALL_BF16.with_(l_glo=400, tree_size=40), 16, 4),
+    ("deep-10-tiles", SMALL_BF16.with_(l_glo=590, tree_size=48), 16, 4),
+    ("deep-13-tiles-2-splits", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 8),
+    ("deep-hd64", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=8, head_dim=64, l_glo=520, tree_size=40), 16, 8),
+    ("deep-f32-hd128", SMALL_BF16.with_(dtype="f32", l_glo=560, tree_size=40), 16, 4),
+    ("deep-seg48-3-row-tiles", SMALL_BF16.with_(l_glo=600, tree_size=96, max_depth=10), 48, 4),
+    ("deep-seg64-two-row-tiles-per-wave", SMALL_BF16.with_(l_glo=600, tree_size=128, max_depth=10), 64, 4),
+])
+def test_long_kv_splits(name, cfg, seg, wgs, monkeypatch):
+    """Tree attention with many tiles per workgroup (the split plan is steered through its tuning knob)."""
+    monkeypatch.setenv("FLOWSPEC_ATTN_WGS", str(wgs))
+    _check_stage(cfg.with_(name=name, seg_len=seg), 5, seg)
