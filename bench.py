@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P1", "P2"])
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug only; invalidates the metric)")
+    ap.add_argument("--seg-len", type=int, default=0, help="override the segment length l_s (debug only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-head", action="store_true", help="time the stage forward alone (an intermediate stage)")
     ap.add_argument("--weights", default="dense", choices=["dense", "int4"],
@@ -83,6 +84,8 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers)
+    if args.seg_len:
+        cfg = cfg.with_(seg_len=args.seg_len)
     seed = 0
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
