@@ -76,7 +76,7 @@ def test_accept_reports_broken_topology_without_touching_outputs():
     assert g_res.n_acc == -1
 
 
-@pytest.mark.parametrize("rows,vocab", [(1, 1), (3, 7), (16, 1024), (24, 32000), (5, 152064), (64, 32001)])
+@pytest.mark.parametrize("rows,vocab", [(1, 1), (3, 7), (16, 1024), (24, 32000), (5, 152064), (64, 32001), (70, 32000), (100, 4100)])
 def test_argmax_from_logits_bit_exact_with_ties(rows, vocab):
     print(f"[case] rows={rows} vocab={vocab}", flush=True)
     lg = synth.random_logits(rows, vocab, 3, rows)
