@@ -533,6 +533,10 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
     const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
     const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
+    // In between (33 .. 127 stacked rows) the few-row kernel re-reads the activations once per workgroup and is bound by the
+    // L2; the gate/up projection (and the LM head) then go through the many-row kernel with 128-feature blocks, which works
+    // out its own RMSNorm scale; the other projections stay with the few-row kernel.
+    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 33);
     const bool handover = w4 || wide;
     float* sspa = st->at<float>(L.off_sspa);
     float* sspb = st->at<float>(L.off_sspb);
@@ -570,7 +574,7 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
         g.X = hb; g.x_frag = 1; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
         g.ssp_in = sspb; g.ssp_n = res_parts; g.ssp_stride = L.ssp_stride;
-        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s, wide));
+        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s, wide || mid));
         // down projection + residual
         g = GemmArgs{};
         g.X = act; g.x_frag = 1; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
@@ -607,7 +611,7 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     const GemmPlan& p = st->L.head;
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
-    const bool wide = !p.w4 && st->d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
+    const bool wide = !p.w4 && st->d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 33);  // many-row kernel (see verify_batch)
     if (p.w4 || wide) {  // (gained) fragment-major copy of the rows + their sums of squares, as at the entry of such a stage
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);

@@ -17,6 +17,11 @@
 #include "gemm.hpp"
 
 
+typedef __attribute__((ext_vector_type(2))) bf16_t bf16x2;
+struct bf16x2x4 {
+    bf16x2 v[4];
+};
+
 template <typename T>
 static __device__ __forceinline__ typename Elem<T>::frag_t load_w(const void* p) {
     using frag_t = typename Elem<T>::frag_t;
@@ -398,9 +403,13 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
     const int kt_lo = (int)((long long)a.nkt * ks / k_splits), nkt = (int)((long long)a.nkt * (ks + 1) / k_splits) - kt_lo;  // >= 1 (host)
     const int mt0 = mb * BMT, m_tiles = (a.M + 15) >> 4;
 
-    if (NORM && t < BMT * 16) {
+    // RMSNorm scale of the rows.  The 256-feature blocks have no registers to spare and take it from the partial sums of
+    // squares their producer left (one per workgroup column of that producer: a few dozen independent loads per row); the
+    // 128-feature blocks add the squares up themselves while they stage the activations (see store_x), so that they can
+    // also follow a producer that leaves no such sums.
+    constexpr bool SELF_NORM = NORM && WNT == 2;
+    if (NORM && !SELF_NORM && t < BMT * 16) {
         const int m = min(mt0 * 16 + t, a.M - 1);
-        // a few dozen partial sums per row (one per 256-feature block of the producer): independent loads, unrolled
         float s0 = 0.f, s1 = 0.f;
         int j = 0;
 #pragma unroll 4
@@ -456,9 +465,28 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
 #pragma unroll
         for (int i = 0; i < XL; ++i) xoff[i] += adv;
     };
+    // Self-computed RMSNorm scale: every 16-byte piece of the activations passes through exactly one thread on its way to
+    // LDS (lane (r16, g) carries 8 consecutive k of row r16), which adds its squares up; pieces fetched past the end of the
+    // K range (the ring runs ahead of the loop) are not counted.
+    float ssq[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) ssq[i] = 0.f;
+    int xstored = 0;  // k-tiles handed to LDS so far
     auto store_x = [&](int j, int buf) {
 #pragma unroll
         for (int i = 0; i < XL; ++i) *(frag_t*)(xs[buf] + (size_t)(w + WAVES * i) * 1024 + (size_t)lane * 16) = xr[j][i];
+        if constexpr (SELF_NORM) {
+            const bool counts = xstored < nkt;  // uniform
+#pragma unroll
+            for (int i = 0; i < XL; ++i) {
+                const bf16x2x4 pr = __builtin_bit_cast(bf16x2x4, xr[j][i]);
+                float sq = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sq = __builtin_amdgcn_fdot2_f32_bf16(pr.v[e], pr.v[e], sq, false);
+                ssq[i] += counts ? sq : 0.f;
+            }
+            ++xstored;
+        }
     };
     // Pipeline, k-tile kt: weights in wq[kt % PFW], activations in LDS buffer kt & 1; xr[n % XD] carries k-tile n from
     // memory to LDS (n = kt + 1 .. kt + XD are in registers or in flight when the iteration starts).  One barrier per
@@ -513,6 +541,14 @@ __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel
                 ((f32x4*)part)[(((size_t)ks * m_tiles + mt0 + mt) * nt_all + pt0 + nt) * 64 + lane] = acc[mt][nt];
         }
         return;
+    }
+    if constexpr (SELF_NORM) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const float tot = wave_xor_add(wave_xor_add(ssq[i], 16), 32);
+            if (g == 0) rs_s[(w + WAVES * i) * 16 + r16] = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+        }
+        __syncthreads();
     }
     // ---- epilogue straight from the accumulators -------------------------------------------------------------
     // (residual projections also leave one partial sum of squares per row and workgroup: the waves' shares meet in LDS,
@@ -595,7 +631,10 @@ static int wide_narrow_rows() {
     return v;
 }
 static int env_int(const char* name, int dflt) { const char* e = getenv(name); return e ? atoi(e) : dflt; }
-static WideShape wide_shape(int, int M) { return M < wide_narrow_rows() ? WideShape{8, 2, 4} : WideShape{8, 4, 4}; }
+static WideShape wide_shape(int, int M) {
+    if (M <= 64) return WideShape{4, 2, 4};  // one 64-row block (gate/up and LM head of segments of 33 to 64 rows)
+    return M < wide_narrow_rows() ? WideShape{8, 2, 4} : WideShape{8, 4, 4};
+}
 
 struct WideGrid {
     int n_cols, m_blocks, k_splits;
@@ -662,18 +701,23 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
 
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
     if (!a.x_frag) return hipErrorInvalidValue;
-    const bool narrow = wide_shape(epi, a.M).wnt == 2;
+    const WideShape sh = wide_shape(epi, a.M);
+    const bool narrow = sh.wnt == 2, half = sh.bmt == 4;
     switch (epi) {
         case EPI_QKV:
+            if (half) break;  // up to 64 rows only gate/up and the LM head come here
             return narrow ? launch_wide_shape<EPI_QKV, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_QKV, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_SWIGLU:
+            if (half) return launch_wide_shape<EPI_SWIGLU, 4, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
             return narrow ? launch_wide_shape<EPI_SWIGLU, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_SWIGLU, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_RESID:
+            if (half) break;
             return narrow ? launch_wide_shape<EPI_RESID, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_RESID, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_LOGITS:
+            if (half) return launch_wide_shape<EPI_LOGITS, 4, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
             return narrow ? launch_wide_shape<EPI_LOGITS, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_LOGITS, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
     }
