@@ -431,6 +431,14 @@ int fs_stage_profile_end(fs_stage* st, void* stream, double* total_ms, long long
 }
 
 // dense or 4-bit projection launch, by the stage's weight format
+// One row block of the many-row kernel has a workgroup per 128 features: that is a good launch if they all run at once
+// (at most one per compute unit) or if there are many rounds of them, not if a few compute units get a second one
+// (measured: 296 workgroups, 60 us against 52 us with the few-row kernel; 216 workgroups, 49 against 57 us).
+static bool mid_cols_ok(int n_tiles) {
+    const int n_cols = (n_tiles + 7) / 8;
+    return n_cols <= 256 || n_cols >= 512;
+}
+
 static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s, bool wide = false) {
     if (wide) return launch_gemm_wide(epi, p.NT, p.n_groups * p.NT, g, st->at<float>(st->L.off_part), st->L.part_bytes, s);
     if (p.w4) {
@@ -533,10 +541,11 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
     const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
     const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
-    // In between (33 .. 127 stacked rows) the few-row kernel re-reads the activations once per workgroup and is bound by the
-    // L2; the gate/up projection (and the LM head) then go through the many-row kernel with 128-feature blocks, which works
-    // out its own RMSNorm scale; the other projections stay with the few-row kernel.
-    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 33);
+    // In between (17 .. 127 stacked rows: more than one row tile) the few-row kernel re-reads the activations once per
+    // workgroup and is bound by the L2; the gate/up projection (and the LM head) then go through the many-row kernel with
+    // 128-feature blocks, which works out its own RMSNorm scale; the other projections stay with the few-row kernel.
+    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 17) &&
+                     mid_cols_ok(L.layers[0].gu.n_groups * L.layers[0].gu.NT);
     const bool handover = w4 || wide;
     float* sspa = st->at<float>(L.off_sspa);
     float* sspb = st->at<float>(L.off_sspb);
@@ -611,7 +620,8 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     const GemmPlan& p = st->L.head;
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
-    const bool wide = !p.w4 && st->d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 33);  // many-row kernel (see verify_batch)
+    const bool wide = !p.w4 && st->d.dtype == FS_BF16 &&  // many-row kernel (see verify_batch)
+                      (l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128) || (l_s >= env_int("FLOWSPEC_MID_ROWS", 17) && mid_cols_ok(p.n_groups * p.NT)));
     if (p.w4 || wide) {  // (gained) fragment-major copy of the rows + their sums of squares, as at the entry of such a stage
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);
