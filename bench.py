@@ -94,8 +94,8 @@ def main():
 
     t_setup = time.time()
     B = max(1, args.batch)
-    if B > 1 and (args.temperature > 0 or args.graph or B > fs.FS_MAX_BATCH or B * cfg.seg_len > 1024):
-        print("bench.py: --batch needs greedy acceptance, no --graph, B <= %d and B * segment <= 1024" % fs.FS_MAX_BATCH, file=sys.stderr)
+    if B > 1 and (args.temperature > 0 or B > fs.FS_MAX_BATCH or B * cfg.seg_len > 1024):
+        print("bench.py: --batch needs greedy acceptance, B <= %d and B * segment <= 1024" % fs.FS_MAX_BATCH, file=sys.stderr)
         sys.exit(2)
     w4 = args.weights == "int4"
     up = lambda a: None if a is None else torch.from_numpy(a).to(dev, tdt)
@@ -153,7 +153,12 @@ def main():
         stack_in = [torch.cat([q["hid"][o:o + n] for q in reqs], dim=0).contiguous() for o, n in segs]
         stack_out = [torch.empty_like(x) for x in stack_in]
         stack_logits = torch.zeros((B * cfg.seg_len, max(cfg.vocab, 1)), dtype=torch.float32, device=dev) if use_head else None
-        stack_amax = torch.zeros(B * cfg.seg_len, dtype=torch.int32, device=dev)
+        # argmax rows of a segment arrive stacked [request][row of the segment]; one concatenation per step turns the segments'
+        # arrays into [request][node], and one indexed store plants every request's accepted path
+        seg_amax = [torch.zeros(B * n, dtype=torch.int32, device=dev) for _, n in segs]
+        all_plant_req = torch.cat([torch.full_like(q["plant_rows"], r) for r, q in enumerate(reqs)])
+        all_plant_rows = torch.cat([q["plant_rows"] for q in reqs])
+        all_plant_toks = torch.cat([q["plant_toks"].to(torch.int32) for q in reqs])
     setup_s = time.time() - t_setup
 
     def step_batch():
@@ -162,13 +167,12 @@ def main():
             items = [(q["kv"], l_glo, l_glo + off, off, n, q["tree"].parent[: off + n]) for q in reqs]
             stage.tree_verify_batch(items, stack_in[i], stack_out[i])
             if use_head:
-                stage.tree_logits(stack_out[i], stack_logits[: B * n], stack_amax[: B * n])
-                for r, q in enumerate(reqs):
-                    q["amax"][off:off + n] = stack_amax[r * n:(r + 1) * n]
-        for q in reqs:
-            # planted acceptance, written into the argmax (the logits of a batch stay stacked per segment)
-            q["amax"][q["plant_rows"]] = q["plant_toks"].to(torch.int32)
-            fs.tree_accept(None, q["amax"], q["token"], q["parent"], T, q["res"], q["retain"], q["work"])
+                stage.tree_logits(stack_out[i], stack_logits[: B * n], seg_amax[i])
+        all_amax = torch.cat([a.view(B, -1) for a in seg_amax], dim=1)  # [request][node]
+        # planted acceptance, written into the argmax (the logits of a batch stay stacked per segment)
+        all_amax[all_plant_req, all_plant_rows] = all_plant_toks
+        for r, q in enumerate(reqs):
+            fs.tree_accept(None, all_amax[r], q["token"], q["parent"], T, q["res"], q["retain"], q["work"])
             stage.kv_compact(q["kv"], l_glo, l_glo + T, q["retain"], res=q["res"], new_len=new_len)
             fs.seg_prune(q["hid"][segs[-1][0]:], segs[-1][0], q["retain"], res=q["res"], seg_out=pr_out, l_s_out=pr_n)
 
@@ -202,25 +206,29 @@ def main():
     if args.graph:
         # every launch of the step (the library's kernels take the tree as kernel arguments, nothing is allocated or
         # cleared by memset) goes into one graph on a side stream; a replay is one step
-        step()
+        run()
         torch.cuda.synchronize()
         cap_stream = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=cap_stream):
-            cur = torch.cuda.current_stream().cuda_stream
-            l_glo = cfg.l_glo
-            for i, (off, n) in enumerate(segs):
-                stage.tree_verify_stage(kv, l_glo, l_glo + off, hid_segs[i], off, tree.parent[: off + n], out_segs[i], stream=cur)
+        if B > 1:
+            with torch.cuda.graph(graph, stream=cap_stream):
+                step_batch()  # the binding launches on the current stream, which is the capturing one here
+        else:
+            with torch.cuda.graph(graph, stream=cap_stream):
+                cur = torch.cuda.current_stream().cuda_stream
+                l_glo = cfg.l_glo
+                for i, (off, n) in enumerate(segs):
+                    stage.tree_verify_stage(kv, l_glo, l_glo + off, hid_segs[i], off, tree.parent[: off + n], out_segs[i], stream=cur)
+                    if use_head:
+                        stage.tree_logits(out_segs[i], logits[off:off + n], amax[off:off + n], stream=cur)
                 if use_head:
-                    stage.tree_logits(out_segs[i], logits[off:off + n], amax[off:off + n], stream=cur)
-            if use_head:
-                logits[plant_rows, plant_toks] += 100.0
-                fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work, stream=cur)
-            else:
-                amax[plant_rows] = plant_toks.to(torch.int32)
-                fs.tree_accept(None, amax, token_d, parent_d, T, res, retain, work, stream=cur)
-            stage.kv_compact(kv, l_glo, l_glo + T, retain, res=res, new_len=new_len, stream=cur)
-            fs.seg_prune(hid_segs[-1], segs[-1][0], retain, res=res, seg_out=pr_out, l_s_out=pr_n, stream=cur)
+                    logits[plant_rows, plant_toks] += 100.0
+                    fs.tree_accept(logits, amax, token_d, parent_d, T, res, retain, work, stream=cur)
+                else:
+                    amax[plant_rows] = plant_toks.to(torch.int32)
+                    fs.tree_accept(None, amax, token_d, parent_d, T, res, retain, work, stream=cur)
+                stage.kv_compact(kv, l_glo, l_glo + T, retain, res=res, new_len=new_len, stream=cur)
+                fs.seg_prune(hid_segs[-1], segs[-1][0], retain, res=res, seg_out=pr_out, l_s_out=pr_n, stream=cur)
         run = graph.replay
     for _ in range(args.warmup):
         run()

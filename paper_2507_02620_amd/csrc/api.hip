@@ -191,7 +191,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     L.off_sspb = take(ssp_bytes);
     // many-row segments: scratch for the K-split partial results of the two residual projections
     L.part_bytes = 0;
-    if (d->dtype == FS_BF16 && !w4 && d->max_seg >= 128) L.part_bytes = wide_partial_bytes(d->max_seg);
+    if (d->dtype == FS_BF16 && !w4 && d->max_seg > 16) L.part_bytes = wide_partial_bytes(d->max_seg, d->d_model / 16);
     L.off_part = take(L.part_bytes);
     L.off_krow = take(M * sizeof(unsigned long long));  // cache slot address of every stacked row
     L.off_ancall = take((size_t)d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // masks of every node while a deep tree's are built
@@ -540,12 +540,15 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
     // hand-over of fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
     const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
-    const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128);
-    // In between (17 .. 127 stacked rows: more than one row tile) the few-row kernel re-reads the activations once per
-    // workgroup and is bound by the L2; the gate/up projection (and the LM head) then go through the many-row kernel with
-    // 128-feature blocks, which works out its own RMSNorm scale; the other projections stay with the few-row kernel.
-    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 17) &&
-                     mid_cols_ok(L.layers[0].gu.n_groups * L.layers[0].gu.NT);
+    const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 65);
+    // In between (17 .. 64 stacked rows: more than one row tile, less than a row block and a half) the few-row kernel re-reads
+    // the activations once per workgroup and is bound by the L2; gate/up, the down projection (and the LM head) then go
+    // through the many-row kernel with one 64-row block of 128-feature column blocks, which works out its own RMSNorm scale
+    // (gate/up) or splits K (down); QKV and the attention output have too few column blocks for that and stay with the
+    // few-row kernel.
+    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 17);
+    const bool mid_gu = mid && mid_cols_ok(L.layers[0].gu.n_groups * L.layers[0].gu.NT);
+    const bool mid_down = mid;
     const bool handover = w4 || wide;
     float* sspa = st->at<float>(L.off_sspa);
     float* sspb = st->at<float>(L.off_sspb);
@@ -583,7 +586,7 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
         g.X = hb; g.x_frag = 1; g.ldx = d.d_model; g.M = l_s; g.K = p.gu.K; g.nkt = p.gu.nkt; g.N = 2 * p.gu.N; g.Wp = p.gu.wp; g.eps = d.rms_eps;
         g.act_out = act; g.F = d.d_ffn;
         g.ssp_in = sspb; g.ssp_n = res_parts; g.ssp_stride = L.ssp_stride;
-        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s, wide || mid));
+        HIP_TRY_K(st, FS_K_GATEUP, s, launch_proj(st, EPI_SWIGLU, p.gu, g, s, wide || mid_gu));
         // down projection + residual
         g = GemmArgs{};
         g.X = act; g.x_frag = 1; g.ldx = d.d_ffn; g.M = l_s; g.K = p.down.K; g.nkt = p.down.nkt; g.N = p.down.N; g.Wp = p.down.wp;
@@ -591,7 +594,7 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
         if (handover && !last) {
             g.gain_next = w4 ? gains + (size_t)(2 * l + 2) * d.d_model : nullptr; g.ssp_out = sspa; g.ssp_stride = L.ssp_stride;
         }
-        HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s, wide));
+        HIP_TRY_K(st, FS_K_DOWN, s, launch_proj(st, EPI_RESID, p.down, g, s, wide || mid_down));
     }
     return FS_OK;
 }
@@ -621,7 +624,7 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
     const bool wide = !p.w4 && st->d.dtype == FS_BF16 &&  // many-row kernel (see verify_batch)
-                      (l_s >= env_int("FLOWSPEC_WIDE_ROWS", 128) || (l_s >= env_int("FLOWSPEC_MID_ROWS", 17) && mid_cols_ok(p.n_groups * p.NT)));
+                      (l_s >= env_int("FLOWSPEC_WIDE_ROWS", 65) || (l_s >= env_int("FLOWSPEC_MID_ROWS", 17) && mid_cols_ok(p.n_groups * p.NT)));
     if (p.w4 || wide) {  // (gained) fragment-major copy of the rows + their sums of squares, as at the entry of such a stage
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);

@@ -665,9 +665,12 @@ int wide_ssp_parts(int M, int n_tiles) {  // one per workgroup column of the res
     return (n_tiles + col_tiles - 1) / col_tiles;
 }
 
-size_t wide_partial_bytes(int) {
-    // slices * row tiles * feature tiles KiB, with slices * blocks <= 512: at most 512 blocks' worth of tiles (largest block shape)
-    return (size_t)512 * 8 * 4 * 4 * 1024;
+size_t wide_partial_bytes(int max_rows, int n_tiles) {
+    // slices * row tiles * feature tiles KiB: at most 8 slices of the whole result, and, with slices * blocks bounded by the
+    // split rule, at most 512 blocks' worth of tiles (largest block shape)
+    const size_t whole = (size_t)8 * ((max_rows + 15) / 16) * (size_t)(n_tiles + 15) * 1024;
+    const size_t cap = (size_t)512 * 8 * 4 * 4 * 1024;
+    return whole < cap ? whole : cap;
 }
 
 template <int EPI, int BMT, int WNT, int WAVES>
@@ -705,7 +708,7 @@ hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs&
     const bool narrow = sh.wnt == 2, half = sh.bmt == 4;
     switch (epi) {
         case EPI_QKV:
-            if (half) break;  // up to 64 rows only gate/up and the LM head come here
+            if (half) return launch_wide_shape<EPI_QKV, 4, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
             return narrow ? launch_wide_shape<EPI_QKV, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_QKV, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_SWIGLU:
@@ -713,7 +716,7 @@ hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs&
             return narrow ? launch_wide_shape<EPI_SWIGLU, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_SWIGLU, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_RESID:
-            if (half) break;
+            if (half) return launch_wide_shape<EPI_RESID, 4, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
             return narrow ? launch_wide_shape<EPI_RESID, 8, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s)
                           : launch_wide_shape<EPI_RESID, 8, 4, 4>(layout_nt, n_tiles, a, part, part_bytes, s);
         case EPI_LOGITS:

@@ -89,7 +89,7 @@ hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs&
 // residual projections (wide_partial_bytes gives a sufficient size for segments of up to max_rows rows); a residual
 // projection leaves wide_ssp_parts(M, n_tiles) partial sums of squares per row in ssp_out.
 int wide_ssp_parts(int M, int n_tiles);
-size_t wide_partial_bytes(int max_rows);
+size_t wide_partial_bytes(int max_rows, int n_tiles);
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s);
 // MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);

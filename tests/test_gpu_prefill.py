@@ -19,6 +19,12 @@ def _chain(n):
     (synth.StageConfig("pf-bf16-1024", "bf16", 1, 512, 4, 4, 128, 1024, 0, 0, 1024, 1024, 1024, 1), 1024),
     # feature counts that are not multiples of a workgroup's 256 features: padding tiles in every epilogue and in the K-split fix-up
     (synth.StageConfig("pf-bf16-odd-widths", "bf16", 2, 480, 6, 3, 64, 1056, 0, 33, 150, 150, 150, 1, qkv_bias=True), 150),
+    # one partly filled row block of the many-row kernel (65 .. 127 rows), K slices for the residual projections
+    (synth.StageConfig("pf-bf16-96", "bf16", 2, 1024, 8, 8, 128, 2816, 0, 60, 96, 96, 96, 1), 96),
+    (synth.StageConfig("pf-bf16-81-gqa", "bf16", 2, 512, 8, 2, 64, 1408, 0, 100, 81, 81, 81, 1, qkv_bias=True), 81),
+    # 17 .. 64 rows: gate/up and down projection through one 64-row block, the rest through the few-row kernel
+    (synth.StageConfig("pf-bf16-50", "bf16", 2, 1024, 8, 8, 128, 2816, 0, 60, 50, 50, 50, 1), 50),
+    (synth.StageConfig("pf-bf16-20-odd-widths", "bf16", 2, 480, 6, 3, 64, 1056, 0, 33, 20, 20, 20, 1, qkv_bias=True), 20),
 ])
 def test_chain_segment(cfg, rows):
     from tests.gpu_util import TOL, Pair, max_rel_err
