@@ -162,8 +162,9 @@ int fs_tree_verify_stage(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache
 /*
  * The same forward for a batch of requests that share the stage's weights (data-parallel serving: each request has its own
  * KV cache, tree and context length): the segments' rows are stacked, the projections run once over all of them — the
- * weights are streamed once per batch instead of once per request, and from 128 stacked rows on the projections are bound
- * by the matrix units instead of by the weight stream — and tree attention runs per request inside the same launches.
+ * weights are streamed once per batch instead of once per request, and from a few dozen stacked rows on the projections are
+ * bound by the matrix units and the on-chip caches instead of by the weight stream — and tree attention runs per request
+ * inside the same launches.
  *   items       HOST array [n_items]; each item is one fs_tree_verify_stage call's worth of arguments (kv, l_glo, l_cache,
  *               seg_off, l_s, host parent array); l_s = 0 items are skipped.  All caches must share one set of strides.
  *   hidden_in / hidden_out  device [sum of l_s, d_model], the items' rows in item order; may alias

@@ -84,9 +84,11 @@ hipError_t launch_prenorm(const void* X, int ldx, int M, int K, const void* gain
                              hipStream_t s);
 // 4-bit weights, bf16 activations: w[n][k] = scale[n][k/128] * (code - 8)
 hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);
-// bf16, fragment-major activations: the kernel for segments of 128 rows and more (128-row blocks).  layout_nt and n_tiles describe the re-tiled weights (tiles per group, 16-feature tiles in total);
-// normed projections need ssp_in.  `part` (may be null) is scratch for K-split partial results of the d_model-wide
-// residual projections (wide_partial_bytes gives a sufficient size for segments of up to max_rows rows); a residual
+// bf16, fragment-major activations: the many-row kernel (128-row blocks; one 64-row block up to 64 rows).  layout_nt and n_tiles
+// describe the re-tiled weights (tiles per group, 16-feature tiles in total); normed projections need ssp_in from 384 rows on
+// (256-feature blocks; the 128-feature blocks add up the squares of the activations themselves).  `part` (may be null) is scratch for K-split partial results of the d_model-wide
+// residual projections (wide_partial_bytes gives a sufficient size for segments of up to max_rows rows and n_tiles output
+// tiles); a residual
 // projection leaves wide_ssp_parts(M, n_tiles) partial sums of squares per row in ssp_out.
 int wide_ssp_parts(int M, int n_tiles);
 size_t wide_partial_bytes(int max_rows, int n_tiles);
