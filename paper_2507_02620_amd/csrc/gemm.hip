@@ -350,28 +350,30 @@ hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const G
     return hipErrorInvalidValue;
 }
 
-// ---- many-row segments (chunked prefill): MFMA-bound projection ---------------------------------------------
-// From about 128 rows on, the projections stop being a weight stream and become a matrix product that has to keep
-// the MFMA pipes busy.  Workgroup = 4 waves, block = 128 rows x 256 features, wave w owns features [64w, 64w + 64)
-// for all 128 rows (8 x 4 accumulator tiles).
-//   * Weights are private to a wave, so they skip LDS: each wave streams its four tiles per k-tile straight from
-//     the re-tiled copy into registers, a ring of PFW k-tiles deep (the same coalesced 1 KiB fragment loads as
-//     the few-row kernel).
-//   * Activations are shared by the four waves: the block's 8 fragments per k-tile (fragment-major in memory, so a
-//     plain 8 KiB copy) go through a double-buffered LDS stage, one barrier per k-tile.
-//   Per k-tile and wave: 8 LDS fragment reads + 4 global fragment loads feed 32 MFMAs — half of the LDS and of the
-//   vector-memory bandwidth at full MFMA rate.
-//   * RMSNorm: the row scale comes from partial sums of squares left by the producer of the activations
-//     (GemmArgs::ssp_in), so the loop contains no per-element arithmetic.
+// ---- many-row segments (chunked prefill, stacked requests): projection as a matrix product -------------------
+// With more than a row tile or two the projections stop being a pure weight stream: the few-row kernel re-reads the
+// activations once per workgroup and ends up bound by the path from L2 into the compute units.  This kernel shares the
+// activations between the waves instead.  Workgroup = 4 waves; block = 128 rows x 256 features (from 384 rows), 128 rows
+// x 128 features (65 .. 383 rows) or 64 rows x 128 features (up to 64 rows); wave w owns a quarter of the features for
+// all rows of the block (8 x 4, 8 x 2 or 4 x 2 accumulator tiles).
+//   * Weights are private to a wave, so they skip LDS: each wave streams its tiles per k-tile straight from the re-tiled
+//     copy into registers, a ring of PFW k-tiles deep (the same coalesced 1 KiB fragment loads as the few-row kernel).
+//   * Activations are shared by the four waves: the block's fragments per k-tile (fragment-major in memory, so a plain
+//     copy of 8 or 4 KiB) go through a double-buffered LDS stage, one barrier per k-tile.
+//   Per k-tile and wave of the largest block: 8 LDS fragment reads + 4 global fragment loads feed 32 MFMAs — half of the
+//   LDS and of the vector-memory bandwidth at full MFMA rate.  What binds it there is the L2: every k-tile of a block
+//   asks it for 24 KiB (16 KiB of weights, 8 KiB of activations) per 2.1 MFLOP.
+//   * RMSNorm: the 256-feature blocks take the row scale from partial sums of squares left by the producer of the
+//     activations (GemmArgs::ssp_in), so their loop contains no per-element arithmetic; the 128-feature blocks have
+//     registers to spare and add the squares up while they stage the activations.
 //   * Workgroups that share weights (the row blocks of one feature block) get consecutive slots on one XCD, so the
 //     weights are fetched from HBM once and hit in that XCD's L2 afterwards.
-
 //   * Projections too narrow to fill the chip (d_model outputs, a few row blocks) split K over `k_splits` workgroups;
 //     each writes its raw accumulator tiles (MFMA lane order, so 16 bytes per lane, contiguous per wave) to a scratch
 //     array and wide_fixup_kernel adds them up and runs the residual epilogue.
-//   * The block shape is a template parameter.  64-row blocks with 2 waves x 2 tiles per workgroup were tried for segments of
-//     33 to 127 rows and lost to the few-row kernel (64 rows: QKV 37 -> 75 us, gate/up 49 -> 91 us): a wave then has only 8
-//     MFMAs per k-tile to hide a barrier and an LDS round trip behind.
+//   * Which projections come here at which row count is the caller's choice (with one 64-row block: gate/up, the down
+//     projection and the LM head; QKV and the attention output have too few 128-feature blocks to fill the chip and a
+//     wave has only 8 MFMAs per k-tile to hide a barrier and an LDS round trip behind: 64 rows, QKV 31 -> 38 us).
 template <int EPI, bool PARTIAL, int BMT, int WNT, int WAVES, bool STREAMW>
 __global__ void __launch_bounds__(WAVES * 64, BMT == 8 ? 2 : 3) wide_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
                                                            float* part) {
