@@ -430,7 +430,6 @@ int fs_stage_profile_end(fs_stage* st, void* stream, double* total_ms, long long
     return FS_OK;
 }
 
-// dense or 4-bit projection launch, by the stage's weight format
 // One row block of the many-row kernel has a workgroup per 128 features: that is a good launch if they all run at once
 // (at most one per compute unit) or if there are many rounds of them, not if a few compute units get a second one
 // (measured: 296 workgroups, 60 us against 52 us with the few-row kernel; 216 workgroups, 49 against 57 us).
@@ -439,6 +438,7 @@ static bool mid_cols_ok(int n_tiles) {
     return n_cols <= 256 || n_cols >= 512;
 }
 
+// dense or 4-bit projection launch, by the stage's weight format; `wide`: through the many-row kernel
 static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s, bool wide = false) {
     if (wide) return launch_gemm_wide(epi, p.NT, p.n_groups * p.NT, g, st->at<float>(st->L.off_part), st->L.part_bytes, s);
     if (p.w4) {
@@ -536,7 +536,7 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
 
     // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
     // travel beside them as partial sums (see GemmArgs::gain_next)
-    // 128 rows and more (chunked prefill, batches of segments) take the MFMA-bound projection kernel; it uses the same
+    // 65 rows and more (chunked prefill, batches of segments) take the many-row projection kernel; it uses the same
     // hand-over of fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
     const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
