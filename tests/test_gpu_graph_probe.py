@@ -60,6 +60,54 @@ def test_verify_and_logits_replay_from_a_graph():
             assert torch.equal(g, w), f"replay {rep}: tensor {k} differs from the eager run"
 
 
+@pytest.mark.parametrize("n_req", [3, 6])
+def test_batched_verify_replays_from_a_graph(n_req):
+    """The batched forward under capture: 3 requests x 16 rows take the few-row kernel plus the one-block many-row route for
+    gate/up and the down projection, 6 x 16 rows the many-row kernel with K slices and the fix-up pass.  Three replays with
+    eager work in between reproduce the eager hidden states and caches bit for bit."""
+    import torch
+    from paper_2507_02620_amd import flowspec as fs
+    from tests.gpu_util import to_dev
+    cfg = synth.StageConfig("graph-batch", "bf16", 2, 512, 4, 2, 128, 1408, 0, 90, 16, 16, 5, 3)
+    print(f"[case] {cfg.name} requests={n_req}", flush=True)
+    dev = "cuda"
+    layers = [{k: (None if v is None else to_dev(v, torch.bfloat16)) for k, v in synth.layer_weights(cfg, l, 11).items()}
+              for l in range(cfg.n_layers)]
+    stage = fs.stage_from_config(cfg, layers, max_seg=n_req * cfg.seg_len)
+    kvs, trees = [], []
+    for r in range(n_req):
+        kv = stage.new_kv_cache()
+        for l in range(cfg.n_layers):
+            kv[l, :, :, : cfg.l_glo] = to_dev(synth.prefix_kv(cfg, l, cfg.kv_capacity, 11 + r)[:, :, : cfg.l_glo], torch.bfloat16)
+        kvs.append(kv)
+        trees.append(synth.random_tree(cfg.tree_size, cfg.max_depth, cfg.max_branch, 1000, 11, stream=r))
+    hid = torch.cat([to_dev(synth.hidden(cfg, cfg.tree_size, r, 11), torch.bfloat16) for r in range(n_req)], dim=0).contiguous()
+    out = torch.empty_like(hid)
+    kv0 = [kv.clone() for kv in kvs]
+    items = [(kvs[r], cfg.l_glo, cfg.l_glo, 0, cfg.tree_size, trees[r].parent) for r in range(n_req)]
+
+    stage.tree_verify_batch(items, hid, out)
+    torch.cuda.synchronize()
+    want = [out.clone()] + [kv.clone() for kv in kvs]
+
+    for kv, k0 in zip(kvs, kv0):
+        kv.copy_(k0)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        stage.tree_verify_batch(items, hid, out, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        for kv, k0 in zip(kvs, kv0):
+            kv.copy_(k0)
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, (g, w) in enumerate(zip([out] + kvs, want)):
+            assert torch.equal(g, w), f"replay {rep}: tensor {k} differs from the eager run"
+
+
 def test_probes_report_plausible_rates():
     import torch
     from paper_2507_02620_amd import flowspec as fs
