@@ -78,7 +78,8 @@ typedef struct {
 /* KV cache, device, element type desc.dtype.  Element (layer, kv, head, slot, t) is at
  * base + layer*stride_layer + kv*stride_kv + head*stride_head + slot*stride_tok + t   (strides in elements,
  * kv = 0 for K — stored after rotation — and 1 for V).  stride_tok must be a multiple of 8 (bf16) / 4 (f32)
- * elements and base 16-byte aligned.  Slots [0, l_cache) are valid. */
+ * elements and base 16-byte aligned; one head's slots must span less than 4 GiB (kv_capacity * stride_tok * element size),
+ * else FS_EINVAL.  Slots [0, l_cache) are valid. */
 typedef struct {
     void *base;
     long long stride_layer, stride_kv, stride_head, stride_tok;

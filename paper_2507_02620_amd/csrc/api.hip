@@ -203,6 +203,8 @@ int valid_kv(const fs_stage_desc& d, const fs_kv_cache& kv) {
     if (!kv.base || ((uintptr_t)kv.base & 15)) return FS_EINVAL;
     if (kv.stride_tok < d.head_dim || kv.stride_tok % epf || kv.stride_head % epf || kv.stride_kv % epf || kv.stride_layer % epf) return FS_EINVAL;
     if (kv.stride_head < 0 || kv.stride_kv < 0 || kv.stride_layer < 0) return FS_EINVAL;
+    // tree attention addresses the slots of one head with 32-bit byte offsets
+    if ((long long)d.kv_capacity * kv.stride_tok * elem >= (1LL << 32)) return FS_EINVAL;
     return FS_OK;
 }
 
