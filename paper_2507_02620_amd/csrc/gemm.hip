@@ -706,6 +706,9 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
 
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
     if (!a.x_frag) return hipErrorInvalidValue;
+    // the kernel addresses weights and activations with 32-bit byte offsets from their bases
+    if ((unsigned long long)(n_tiles + layout_nt) * a.nkt * 1024ull >= (1ull << 32) || (unsigned long long)(a.M + 16) * a.nkt * 64ull >= (1ull << 32))
+        return hipErrorInvalidValue;
     const WideShape sh = wide_shape(epi, a.M);
     const bool narrow = sh.wnt == 2, half = sh.bmt == 4;
     switch (epi) {
