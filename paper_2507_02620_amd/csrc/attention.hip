@@ -25,6 +25,8 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
 #ifndef PADK
 #define PADK 8   /* elements; keeps K rows 16-byte aligned and spreads LDS banks */
 #endif
@@ -201,8 +203,24 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
         }
     };
 
-    // one tile from the staged copy in LDS
-    auto process = [&](int tile) {
+    // The two words of every row's ancestor mask that cover a tile's draft slots, fetched ahead of the tile's refill in the
+    // masked part of the tile range (below): a wait for them then leaves the refill in flight.
+    const uint64_t* am[MTW];
+#pragma unroll
+    for (int i = 0; i < MTW; ++i) am[i] = a.anc + (size_t)seg_r[i] * FS_ANC_WORDS;
+    uint64_t mw0[MTW], mw1[MTW];
+    auto load_mask = [&](int tile) {
+        const int wd = min(max((tile * BS - l_glo) >> 6, 0), FS_ANC_WORDS - 1), wd1 = min(wd + 1, FS_ANC_WORDS - 1);
+#pragma unroll
+        for (int i = 0; i < MTW; ++i) {
+            mw0[i] = am[i][wd];
+            mw1[i] = am[i][wd1];
+        }
+    };
+
+    // one tile from the staged copy in LDS; MASKED: the tile may touch draft slots (its mask words are in mw0 / mw1)
+    auto process = [&](int tile, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         const int s0 = tile * BS;
         if (!computes) return;
 
@@ -210,21 +228,20 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
         // (slots below l_glo are always visible; draft slot l_glo + j by bit j of the row's ancestor mask; slots
         // beyond L never).  Tiles below l_glo need no mask; a wave none of whose rows sees any slot of the tile
         // skips it (deep chains: the upper triangle).
-        const bool need_mask = (s0 + BS > l_glo);  // tile touches draft slots or the tail beyond L
+        const bool need_mask = MASKED && (s0 + BS > l_glo);  // tile touches draft slots or the tail beyond L
         uint64_t vm[MTW];
         if (need_mask) {
             const int d0 = s0 - l_glo, valid = L - s0;  // valid >= 1
             bool any = false;
 #pragma unroll
             for (int i = 0; i < MTW; ++i) {
-                const uint64_t* am = a.anc + (size_t)seg_r[i] * FS_ANC_WORDS;
                 uint64_t m;
                 if (d0 >= 0) {
                     const int wd = d0 >> 6, sh = d0 & 63;
-                    m = am[wd] >> sh;
-                    if (sh && wd + 1 < FS_ANC_WORDS) m |= am[wd + 1] << (64 - sh);
+                    m = mw0[i] >> sh;
+                    if (sh && wd + 1 < FS_ANC_WORDS) m |= mw1[i] << (64 - sh);
                 } else {
-                    m = ((1ull << (-d0)) - 1) | (am[0] << (-d0));  // 0 < -d0 < BS <= 64
+                    m = ((1ull << (-d0)) - 1) | (mw0[i] << (-d0));  // 0 < -d0 < BS <= 64
                 }
                 if (valid < 64) m &= (1ull << valid) - 1;
                 if (!rok[i]) m = 0;
@@ -344,31 +361,50 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
     // Wait here for every load issued so far (Q fragments, first tiles): inside the loop the only vector-memory loads left to
     // wait for are then tile fetches.
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
-    // Steady state: every tile of the group has a successor NSET tiles ahead, so store-and-refill is straight-line code
-    // and the wait before a store counts exactly the loads of the other register set that may stay in flight (a
+    // The tile range has an unmasked part (slots below l_glo: [t0, tA)) and a masked part ([tA, t1): draft slots and the
+    // tail beyond L); tA sits on a register-set boundary, so the masked part may begin with a tile that needs no mask.
+    using unmasked_t = std::integral_constant<bool, false>;
+    using masked_t = std::integral_constant<bool, true>;
+    const int t_mask = max(t0, min(t1, l_glo / BS));
+    const int tA = t0 + (t_mask - t0) / NSET * NSET;
+    // Unmasked, steady state: every tile of the group has a successor NSET tiles ahead, so store-and-refill is straight-line
+    // code and the wait before a store counts exactly the loads of the other register set that may stay in flight (a
     // conditional refill would make the compiler wait for all of them, and the compute phase would never overlap a fetch).
     int tile = t0;
-    for (; tile + 2 * NSET <= t1; tile += NSET) {
+    for (; tile + 2 * NSET <= t1 && tile + NSET <= tA; tile += NSET) {
 #pragma unroll
         for (int k = 0; k < NSET; ++k) {
             __syncthreads();  // previous tile fully consumed
             stash(kregs[k], vregs[k]);
             fetch(tile + k + NSET, kregs[k], vregs[k]);  // in flight across the barriers and the next NSET tiles
             __syncthreads();
-            process(tile + k);
+            process(tile + k, unmasked_t{});
         }
     }
-    // Tail: the last tiles (fewer than 2 * NSET), refilled only while a successor exists.
+    // Unmasked, last tiles of a range without a masked part: refilled only while a successor exists.
+    for (; tile < tA; tile += NSET) {
+#pragma unroll
+        for (int k = 0; k < NSET; ++k) {
+            __syncthreads();
+            stash(kregs[k], vregs[k]);
+            if (tile + k + NSET < t1) fetch(tile + k + NSET, kregs[k], vregs[k]);
+            __syncthreads();
+            process(tile + k, unmasked_t{});
+        }
+    }
+    // Masked part, straight-line as well: the mask words are fetched before the refill, the refill is never skipped (past
+    // the end it re-reads the range's last tile, a handful of loads that hit in L2), and a tile beyond the end only skips
+    // its arithmetic.
     for (; tile < t1; tile += NSET) {
 #pragma unroll
         for (int k = 0; k < NSET; ++k) {
-            if (tile + k < t1) {  // uniform over the workgroup
-                __syncthreads();
-                stash(kregs[k], vregs[k]);
-                if (tile + k + NSET < t1) fetch(tile + k + NSET, kregs[k], vregs[k]);
-                __syncthreads();
-                process(tile + k);
-            }
+            const bool live = tile + k < t1;  // uniform over the workgroup
+            __syncthreads();
+            stash(kregs[k], vregs[k]);
+            load_mask(min(tile + k, t1 - 1));
+            fetch(min(tile + k + NSET, t1 - 1), kregs[k], vregs[k]);
+            __syncthreads();
+            if (live) process(tile + k, masked_t{});
         }
     }
 
