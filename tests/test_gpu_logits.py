@@ -12,6 +12,9 @@ pytestmark = pytest.mark.gpu
     (synth.StageConfig("lg-bf16", "bf16", 1, 512, 4, 4, 128, 1376, 32000, 8, 16, 24, 4, 3), 24),
     (synth.StageConfig("lg-bf16-odd-vocab", "bf16", 1, 1024, 8, 2, 128, 1376, 50257, 8, 16, 64, 4, 3), 64),
     (synth.StageConfig("lg-f32", "f32", 1, 256, 4, 4, 64, 688, 1000, 8, 16, 5, 4, 3), 5),
+    # LM head through the many-row kernel: one 64-row block (40 rows), one partly filled 128-row block with padding tiles (100 rows)
+    (synth.StageConfig("lg-bf16-40", "bf16", 1, 512, 4, 4, 128, 1376, 32000, 8, 16, 40, 4, 3), 40),
+    (synth.StageConfig("lg-bf16-100-odd-vocab", "bf16", 1, 1024, 8, 2, 128, 1376, 50257, 8, 16, 100, 4, 3), 100),
 ])
 def test_logits_and_argmax(cfg, rows):
     import torch
