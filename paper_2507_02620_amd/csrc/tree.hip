@@ -110,8 +110,37 @@ __global__ void __launch_bounds__(1024) tree_prepare_deep_kernel(const IdxList p
     }
 }
 
+// A chain (parent[i] = i - 1: a chunk of a prompt rather than a tree) needs no walk at all: node i sees nodes 0 .. i and
+// sits at depth i.  One thread per mask word / rotary pair, as many workgroups as that takes.
+__global__ void __launch_bounds__(256) tree_prepare_chain_kernel(int l_glo, int seg_off, int l_s, int hd, const double* __restrict__ inv_freq,
+                                                                 uint64_t* __restrict__ anc, float2* __restrict__ rope, KRowArgs kr) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < l_s) kr.krow[e] = kr.base + (unsigned long long)(kr.slot0 + e) * kr.tok_bytes;
+    if (e < l_s * FS_ANC_WORDS) {
+        const int i = seg_off + e / FS_ANC_WORDS, w = e % FS_ANC_WORDS;
+        anc[e] = w < (i >> 6) ? ~0ull : (w == (i >> 6) ? ((2ull << (i & 63)) - 1) : 0ull);
+    }
+    const int half = hd >> 1;
+    if (e < l_s * half) {
+        const int r = e / half, t = e % half;
+        const double two_pi = 6.283185307179586476925286766559;
+        double ang = (double)(l_glo + seg_off + r) * inv_freq[t];
+        ang -= two_pi * floor(ang / two_pi);
+        float sn, cs;
+        sincosf((float)ang, &sn, &cs);
+        rope[e] = make_float2(cs, sn);
+    }
+}
+
 hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq,
                                uint64_t* anc_all, uint64_t* anc, float2* rope, const KRowArgs& kr, hipStream_t s) {
+    bool chain = max_depth > 32;  // only worth looking for where the pointer-doubling kernel would run
+    for (int i = 0; chain && i < seg_off + l_s; ++i) chain = parent.v[i] == i - 1;
+    if (chain) {
+        const int n = l_s * (FS_ANC_WORDS > hd / 2 ? FS_ANC_WORDS : hd / 2);
+        hipLaunchKernelGGL(tree_prepare_chain_kernel, dim3((n + 255) / 256), dim3(256), 0, s, l_glo, seg_off, l_s, hd, inv_freq, anc, rope, kr);
+        return hipGetLastError();
+    }
     if (max_depth > 32)
         hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all, anc, rope, kr);
     else
