@@ -450,10 +450,14 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 2, true>), grid, block, 0, s, row_blocks, a);
     else if (MTW == 1 && nw == 4)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 1, true>), grid, block, 0, s, row_blocks, a);
-    else if (MTW == 1 && deep)
+    else if (MTW == 1 && deep && row_blocks == 1)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 2, true>), grid, block, 0, s, row_blocks, a);
-    else if (MTW == 1)
+    else if (MTW == 1 && deep)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 2, false>), grid, block, 0, s, row_blocks, a);
+    else if (MTW == 1 && row_blocks == 1)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 1, true>), grid, block, 0, s, row_blocks, a);
+    else if (MTW == 1)
+        hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 8, 1, false>), grid, block, 0, s, row_blocks, a);
     else if (nw == 4)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 2, 4, 1, true>), grid, block, 0, s, row_blocks, a);
     else if (row_blocks == 1)
@@ -475,9 +479,10 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
                int* tiles_per_split) {
     const int R = G * M, mtiles = (R + 15) / 16;
-    // up to 8 compute waves per workgroup; from 4 row tiles on every wave takes 2 of them (each K/V fragment read from LDS
-    // then serves 32 rows)
-    int mtw = mtiles >= 4 ? 2 : 1;
+    // up to 8 compute waves per workgroup; with 4 to 16 row tiles every wave takes 2 of them (each K/V fragment read from
+    // LDS then serves 32 rows; 64 rows at a 16k context: 64.5 -> 62.8 us).  Beyond that there are row blocks enough to fill
+    // the chip with few or no KV splits, and one tile per wave is faster (1024-row chunk: 74 -> 65 us, no merge pass).
+    int mtw = (mtiles >= 4 && mtiles <= 16) ? 2 : 1;
     if (const char* e = getenv("FLOWSPEC_ATTN_MTW")) mtw = (atoi(e) >= 2 && mtiles > 1) ? 2 : 1;
     int nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
