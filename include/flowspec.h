@@ -144,9 +144,8 @@ int fs_probe_mfma_bf16(void *scratch, int launches, void *stream, double *tflop_
 int fs_last_hip_error(void);
 
 /*
- * Verification-stage forward (Sec. III-A: "executing the corresponding forward pass during the verification
- * of draft tokens"; a segment carries its tree position IDs and attention mask, both derived here from the
- * parent array).  Runs the stage's layers over segment S[seg_off, seg_off + l_s):
+ * Verification-stage forward (Sec. III-A: the forward pass of this stage's layers over one draft segment; a
+ * segment carries its tree position IDs and attention mask, both derived here from the parent array).  Runs the stage's layers over segment S[seg_off, seg_off + l_s):
  *   per layer: RMSNorm -> Q/K/V projections (+bias) -> rotary embedding at position l_glo + depth(node) ->
  *   K/V of row r stored at slot l_cache + r -> tree attention (row r sees every slot < l_glo and the draft
  *   slots l_glo + j with j an ancestor-or-self of node seg_off + r) -> output projection + residual ->
@@ -179,6 +178,18 @@ typedef struct {
     const int32_t *parent; /* HOST [seg_off + l_s] */
 } fs_batch_item;
 int fs_tree_verify_batch(fs_stage *stage, const fs_batch_item *items, int n_items, const void *hidden_in, void *hidden_out, void *stream);
+
+/*
+ * The tree position IDs and the attention mask of a segment (Sec. III-A names both as part of a draft segment; Sec. III-B:
+ * S is a topological order) exactly as fs_tree_verify_stage derives them from the parent array, for inspection and tests:
+ *   anc   device uint64 [l_s][16]: bit j of row r is set iff S index j is node seg_off + r itself or one of its ancestors
+ *   rope  device float  [l_s][head_dim/2][2]: (cos, sin) of (l_glo + depth(seg_off + r)) * rope_theta^(-2t/head_dim)
+ *   parent HOST [seg_off + l_s]
+ * Same kernels and the same routing (short walk / pointer doubling beyond 32 levels / closed form for a chain) as the
+ * forward; uses the stage's scratch, so it must not overlap other calls on the stage.
+ * Errors: FS_EINVAL, FS_ETOPO, FS_ECAP (tree larger than max_tree, segment longer than max_seg), FS_EHIP.
+ */
+int fs_tree_mask(fs_stage *stage, int l_glo, int seg_off, int l_s, const int32_t *parent, uint64_t *anc, float *rope, void *stream);
 
 /*
  * Last stage's verification output (Sec. III-A, continuous SD step: the next-token distribution sent to the
@@ -259,7 +270,8 @@ int fs_seg_prune(const void *seg_in, int l_s, size_t row_bytes, int off, const i
                  int n_retain_host, void *seg_out, int32_t *l_s_out, void *stream);
 
 /* ---- draft-stage tree bookkeeping on the host (Sec. III-B, III-C, III-D); plain CPU code, no GPU work ---------------
- * The paper keeps the tree structure on the draft stage only and runs these steps on the CPU ("low parallelism");
+ * The paper keeps the tree structure on the draft stage only and runs these steps on the CPU (Sec. III-A: they offer
+ * little parallelism);
  * all arrays below are HOST arrays owned by the caller. */
 
 /*

@@ -194,7 +194,7 @@ void make_layout(const fs_stage_desc* d, Layout& L) {
     if (d->dtype == FS_BF16 && !w4 && d->max_seg > 16) L.part_bytes = wide_partial_bytes(d->max_seg, d->d_model / 16);
     L.off_part = take(L.part_bytes);
     L.off_krow = take(M * sizeof(unsigned long long));  // cache slot address of every stacked row
-    L.off_ancall = take((size_t)d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // masks of every node while a deep tree's are built
+    L.off_ancall = take((size_t)2 * d->max_tree * FS_ANC_WORDS * sizeof(uint64_t));  // two copies of every node's mask while a deep tree's are built
     L.total = off;
 }
 
@@ -242,9 +242,21 @@ struct Profiler {
     }
 };
 
+// Tuning knobs from the environment, read once when the stage is created (a launch never calls getenv).
+struct Tunables {
+    int attn_wgs, attn_mtw, wide_rows, mid_rows;
+    void read() {
+        attn_wgs = env_int("FLOWSPEC_ATTN_WGS", 0);    // > 0: workgroups the attention split plan aims for
+        attn_mtw = env_int("FLOWSPEC_ATTN_MTW", 0);    // > 0: row tiles per wave of the attention kernel
+        wide_rows = env_int("FLOWSPEC_WIDE_ROWS", 65); // stacked rows from which every projection takes the many-row kernel
+        mid_rows = env_int("FLOWSPEC_MID_ROWS", 17);   // ... from which the wide projections do
+    }
+};
+
 struct fs_stage {
     fs_stage_desc d;
     Layout L;
+    Tunables tun;
     unsigned char* ws;
     int elem;
     Profiler prof;
@@ -281,6 +293,7 @@ int fs_stage_create(const fs_stage_desc* desc, const fs_layer_weights* layers, c
     fs_stage* st = new (std::nothrow) fs_stage;
     if (!st) return FS_EINVAL;
     st->d = *desc;
+    st->tun.read();
     st->elem = desc->dtype == FS_F32 ? 4 : 2;
     make_layout(desc, st->L);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < st->L.total) {
@@ -534,7 +547,7 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
         ++rq;
     }
     int aMTW, aRB;
-    attn_plan(st->elem, hd, max_M, G, d.n_kv_heads * n_live, max_L, kMaxSplits, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
+    attn_plan(st->elem, hd, max_M, G, d.n_kv_heads * n_live, max_L, kMaxSplits, st->tun.attn_wgs, st->tun.attn_mtw, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split);
 
     // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
     // travel beside them as partial sums (see GemmArgs::gain_next)
@@ -542,13 +555,13 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
     // hand-over of fragment-major activations + partial sums of squares, without gains (they are folded into the bf16 weights).
     const int l_s = rows;
     const bool w4 = d.weight_format == FS_WFMT_INT4_G128;
-    const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_WIDE_ROWS", 65);
+    const bool wide = !w4 && d.dtype == FS_BF16 && l_s >= st->tun.wide_rows;
     // In between (17 .. 64 stacked rows: more than one row tile, less than a row block and a half) the few-row kernel re-reads
     // the activations once per workgroup and is bound by the L2; gate/up, the down projection (and the LM head) then go
     // through the many-row kernel with one 64-row block of 128-feature column blocks, which works out its own RMSNorm scale
     // (gate/up) or splits K (down); QKV and the attention output have too few column blocks for that and stay with the
     // few-row kernel.
-    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= env_int("FLOWSPEC_MID_ROWS", 17);
+    const bool mid = !w4 && !wide && d.dtype == FS_BF16 && l_s >= st->tun.mid_rows;
     const bool mid_gu = mid && mid_cols_ok(L.layers[0].gu.n_groups * L.layers[0].gu.NT);
     const bool mid_down = mid;
     const bool handover = w4 || wide;
@@ -615,6 +628,32 @@ int fs_tree_verify_stage(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, c
     return verify_batch(st, &it, 1, hidden_in, hidden_out, stream);
 }
 
+int fs_tree_mask(fs_stage* st, int l_glo, int seg_off, int l_s, const int32_t* parent, uint64_t* anc, float* rope, void* stream) {
+    if (!st || l_s < 0 || seg_off < 0 || l_glo < 0) return FS_EINVAL;
+    if (l_s == 0) return FS_OK;
+    if (!parent || !anc || !rope) return FS_EINVAL;
+    const int T = seg_off + l_s;
+    if (T > st->d.max_tree || l_s > st->d.max_seg) return FS_ECAP;
+    if (parent[0] != -1) return FS_ETOPO;
+    short depth[FS_MAX_TREE];
+    int max_depth = 0;
+    depth[0] = 0;
+    for (int j = 1; j < T; ++j) {
+        if (parent[j] < -1 || parent[j] >= j) return FS_ETOPO;
+        depth[j] = parent[j] < 0 ? 0 : (short)(depth[parent[j]] + 1);
+        if (depth[j] > max_depth) max_depth = depth[j];
+    }
+    IdxList pl;
+    int rc = fill_idx(pl, parent, T);
+    if (rc) return rc;
+    const Layout& L = st->L;
+    // the rows' cache-slot table is a by-product of the same kernels: it goes to the stage's own scratch
+    KRowArgs kr{st->at<unsigned long long>(L.off_krow), 0ull, 0ull, 0};
+    HIP_TRY(launch_tree_prepare(pl, max_depth, l_glo, seg_off, l_s, st->d.head_dim, st->at<double>(L.off_invf), st->at<uint64_t>(L.off_ancall), anc,
+                                (float2*)rope, kr, (hipStream_t)stream));
+    return FS_OK;
+}
+
 int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int32_t* amax, void* stream) {
     if (!st || l_s < 0) return FS_EINVAL;
     if (st->d.vocab <= 0) return FS_EINVAL;
@@ -626,7 +665,7 @@ int fs_tree_logits(fs_stage* st, const void* hidden, int l_s, float* logits, int
     GemmArgs g{};
     g.X = hidden; g.ldx = st->d.d_model; g.M = l_s; g.K = p.K; g.nkt = p.nkt; g.N = p.N; g.Wp = p.wp; g.eps = st->d.rms_eps; g.logits = logits;
     const bool wide = !p.w4 && st->d.dtype == FS_BF16 &&  // many-row kernel (see verify_batch)
-                      (l_s >= env_int("FLOWSPEC_WIDE_ROWS", 65) || (l_s >= env_int("FLOWSPEC_MID_ROWS", 17) && mid_cols_ok(p.n_groups * p.NT)));
+                      (l_s >= st->tun.wide_rows || (l_s >= st->tun.mid_rows && mid_cols_ok(p.n_groups * p.NT)));
     if (p.w4 || wide) {  // (gained) fragment-major copy of the rows + their sums of squares, as at the entry of such a stage
         void* hb = st->at<void>(st->L.off_hb);
         float* ssp = st->at<float>(st->L.off_sspa);

@@ -476,14 +476,14 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
     return e;
 }
 
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
-               int* tiles_per_split) {
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int* NWC, int* MTW,
+               int* row_blocks, int* n_splits, int* tiles_per_split) {
     const int R = G * M, mtiles = (R + 15) / 16;
     // up to 8 compute waves per workgroup; with 4 to 16 row tiles every wave takes 2 of them (each K/V fragment read from
     // LDS then serves 32 rows; 64 rows at a 16k context: 64.5 -> 62.8 us).  Beyond that there are row blocks enough to fill
     // the chip with few or no KV splits, and one tile per wave is faster (1024-row chunk: 74 -> 65 us, no merge pass).
     int mtw = (mtiles >= 4 && mtiles <= 16) ? 2 : 1;
-    if (const char* e = getenv("FLOWSPEC_ATTN_MTW")) mtw = (atoi(e) >= 2 && mtiles > 1) ? 2 : 1;
+    if (mtw_override > 0) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
     int nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
     *NWC = nw;
@@ -491,10 +491,9 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);
     const int BS = attn_tile_slots(elem_bytes, hd);
     const int ntiles = (L + BS - 1) / BS;
-    const char* env = getenv("FLOWSPEC_ATTN_WGS");
     // about 2 workgroups per CU for long contexts (C5: 512 best, 384 and 768 +12 %); short ones are latency-bound and
     // do slightly better with fewer, longer splits (C2: 256)
-    const int target = env ? atoi(env) : (ntiles <= 32 ? 256 : 512);
+    const int target = wgs_override > 0 ? wgs_override : (ntiles <= 32 ? 256 : 512);
     int want = (target + Hkv * *row_blocks - 1) / (Hkv * *row_blocks);
     if (want > max_splits) want = max_splits;
     if (want > ntiles) want = ntiles;

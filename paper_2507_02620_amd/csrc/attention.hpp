@@ -31,6 +31,7 @@ struct AttnArgs {
 // slots per LDS tile for a given element size and head dim
 static inline int attn_tile_slots(int elem_bytes, int hd) { return elem_bytes * hd >= 512 ? 32 : 64; }
 
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int* NWC, int* MTW, int* row_blocks, int* n_splits,
-               int* tiles_per_split);
+// wgs_override / mtw_override > 0 replace the plan's own choice of the workgroup target and of the row tiles per wave (tuning knobs)
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int* NWC, int* MTW,
+               int* row_blocks, int* n_splits, int* tiles_per_split);
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s);

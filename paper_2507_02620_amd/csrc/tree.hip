@@ -56,48 +56,58 @@ __global__ void __launch_bounds__(256) tree_prepare_kernel(const IdxList parent,
     }
 }
 
-// Deep trees (chains of hundreds of nodes: chunked prefill): walking to the root costs one dependent step per level, so
-// the masks and depths are built by pointer doubling instead — thread i owns node i; A[i] is the set of nodes from i up
-// to (excluding) J[i], D[i] the number of edges between them; each round ORs in A[J[i]] and jumps J[i] <- J[J[i]].
-// A lives in global scratch (T x 16 words).  The OR runs in place: a concurrent reader sees the old or the new word of
-// A[J[i]], and either contains the nodes from J[i] up to the old J[J[i]] and nothing but ancestors, which is all the next
-// round relies on.  J and D are updated behind a barrier.
+// Deep trees (more than 32 levels): walking to the root costs one dependent step per level, so the masks and depths are
+// built by pointer doubling instead — thread i owns node i; A[i] is the set of nodes from i up to (excluding) J[i], D[i] the
+// number of edges between them; each round forms A'[i] = A[i] | A[J[i]] and jumps J[i] <- J[J[i]], D[i] += D[J[i]].
+// A lives in global scratch as two copies of T x 16 words: a round reads one copy and writes the other (every row is
+// rewritten in full, rows that have reached the root are carried over), and J / D are read into registers before the
+// barrier that precedes their update, so no location is read and written between the same two barriers.
 __global__ void __launch_bounds__(1024) tree_prepare_deep_kernel(const IdxList parent, int l_glo, int seg_off, int l_s, int hd,
-                                                                 const double* __restrict__ inv_freq, uint64_t* A,
+                                                                 const double* __restrict__ inv_freq, uint64_t* A0, uint64_t* A1,
                                                                  uint64_t* __restrict__ anc, float2* __restrict__ rope, KRowArgs kr) {
     for (int r = threadIdx.x; r < l_s; r += blockDim.x) kr.krow[r] = kr.base + (unsigned long long)(kr.slot0 + r) * kr.tok_bytes;
     __shared__ short J[1024];
     __shared__ int D[1024];
     const int T = seg_off + l_s, i = threadIdx.x;
+    const int wi = i >> 6;  // ancestors of i are <= i: words above wi stay zero in both copies
     if (i < T) {
         const int p = parent.v[i];
         J[i] = (short)p;
         D[i] = p >= 0 ? 1 : 0;
-        for (int w = 0; w < FS_ANC_WORDS; ++w) A[(size_t)i * FS_ANC_WORDS + w] = (w == (i >> 6)) ? (1ull << (i & 63)) : 0ull;
+        for (int w = 0; w < FS_ANC_WORDS; ++w) {
+            A0[(size_t)i * FS_ANC_WORDS + w] = (w == wi) ? (1ull << (i & 63)) : 0ull;
+            A1[(size_t)i * FS_ANC_WORDS + w] = 0ull;
+        }
     }
     __syncthreads();
+    uint64_t* cur = A0;
+    uint64_t* nxt = A1;
     for (int span = 1; span < T; span <<= 1) {  // after the round every A[i] covers 2 * span levels (or reaches the root)
         const int j = (i < T) ? J[i] : -1;
         int jn = -1, dn = 0;
-        if (j >= 0) {
-            uint64_t add[FS_ANC_WORDS];  // ancestors of j are <= j: higher words stay as they are
-#pragma unroll
-            for (int w = 0; w < FS_ANC_WORDS; ++w) add[w] = (w <= (j >> 6)) ? A[(size_t)j * FS_ANC_WORDS + w] : 0ull;
-#pragma unroll
-            for (int w = 0; w < FS_ANC_WORDS; ++w)
-                if (add[w]) A[(size_t)i * FS_ANC_WORDS + w] |= add[w];
-            jn = J[j];
-            dn = D[i] + D[j];
+        if (i < T) {
+            for (int w = 0; w <= wi; ++w) {
+                uint64_t v = cur[(size_t)i * FS_ANC_WORDS + w];
+                if (j >= 0 && w <= (j >> 6)) v |= cur[(size_t)j * FS_ANC_WORDS + w];
+                nxt[(size_t)i * FS_ANC_WORDS + w] = v;
+            }
+            if (j >= 0) {
+                jn = J[j];
+                dn = D[i] + D[j];
+            }
         }
-        __syncthreads();
+        __syncthreads();  // every read of J, D and of the current copy is done
         if (j >= 0) {
             J[i] = (short)jn;
             D[i] = dn;
         }
-        __syncthreads();
+        uint64_t* t = cur;
+        cur = nxt;
+        nxt = t;
+        __syncthreads();  // the new copy, J and D are visible to the whole workgroup
     }
     for (int e = i; e < l_s * FS_ANC_WORDS; e += blockDim.x)
-        anc[e] = A[(size_t)(seg_off + e / FS_ANC_WORDS) * FS_ANC_WORDS + e % FS_ANC_WORDS];
+        anc[e] = cur[(size_t)(seg_off + e / FS_ANC_WORDS) * FS_ANC_WORDS + e % FS_ANC_WORDS];
     const int half = hd >> 1;
     for (int e = i; e < l_s * half; e += blockDim.x) {
         const int r = e / half, t = e % half;
@@ -142,7 +152,8 @@ hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, 
         return hipGetLastError();
     }
     if (max_depth > 32)
-        hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all, anc, rope, kr);
+        hipLaunchKernelGGL(tree_prepare_deep_kernel, dim3(1), dim3(1024), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc_all,
+                           anc_all + (size_t)(seg_off + l_s) * FS_ANC_WORDS, anc, rope, kr);
     else
         hipLaunchKernelGGL(tree_prepare_kernel, dim3(1), dim3(256), 0, s, parent, l_glo, seg_off, l_s, hd, inv_freq, anc, rope, kr);
     return hipGetLastError();

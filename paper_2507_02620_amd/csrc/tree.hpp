@@ -27,7 +27,8 @@ struct KRowArgs {
 };
 
 // anc [l_s][FS_ANC_WORDS], rope [l_s][hd/2], kr.krow [l_s]; max_depth (of the tree, from the host's validation pass) picks the walking kernel
-// or, for deep trees, the pointer-doubling one, which needs anc_all [seg_off + l_s][FS_ANC_WORDS] as scratch.
+// or, for deep trees, the pointer-doubling one, which needs anc_all [2][seg_off + l_s][FS_ANC_WORDS] as scratch (two copies: each
+// round reads one and writes the other).
 hipError_t launch_tree_prepare(const IdxList& parent, int max_depth, int l_glo, int seg_off, int l_s, int hd, const double* inv_freq,
                                uint64_t* anc_all, uint64_t* anc, float2* rope, const KRowArgs& kr, hipStream_t s);
 hipError_t launch_argmax(const float* logits, int rows, int vocab, int chunks, int32_t* work, int32_t* amax, hipStream_t s);

@@ -24,7 +24,7 @@ _ERR = {FS_EINVAL: "FS_EINVAL", FS_ETOPO: "FS_ETOPO", FS_ECAP: "FS_ECAP", FS_EDT
 KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "argmax", "compact")
 
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
-           "fs_stage_profile_end", "fs_tree_verify_stage", "fs_tree_verify_batch",
+           "fs_stage_profile_end", "fs_tree_verify_stage", "fs_tree_verify_batch", "fs_tree_mask",
            "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
            "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16")
 
@@ -85,6 +85,7 @@ def _load():
     lib.fs_tree_verify_stage.argtypes = [vp, KVCache, ci, ci, vp, ci, ci, i32p, vp, vp]
     lib.fs_tree_verify_batch.argtypes = [vp, C.POINTER(BatchItem), ci, vp, vp, vp]
     lib.fs_tree_logits.argtypes = [vp, vp, ci, vp, vp, vp]
+    lib.fs_tree_mask.argtypes = [vp, ci, ci, ci, i32p, vp, vp, vp]
     lib.fs_tree_accept.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, vp]
     lib.fs_tree_accept_sample.argtypes = [vp, ci, C.c_float, vp, vp, ci, ci, C.c_uint64, C.c_uint64, vp, vp, vp, vp]
     lib.fs_accept_result_to_host.argtypes = [vp, vp, ci, C.POINTER(AcceptResult), i32p, vp]
@@ -214,6 +215,15 @@ class Stage:
             arr[i] = BatchItem(kv_descriptor(kv), int(l_glo), int(l_cache), int(seg_off), int(l_s), par.ctypes.data_as(C.POINTER(C.c_int32)))
         _check(_lib.fs_tree_verify_batch(self._handle, arr, len(items), _dp(hidden_in), _dp(hidden_out), _stream(stream)), "fs_tree_verify_batch")
         return hidden_out
+
+    def tree_mask(self, l_glo, seg_off, l_s, parent, stream=None):
+        """(anc int64 [l_s, 16] holding the uint64 mask words, rope float32 [l_s, head_dim/2, 2]) of a segment, as the forward derives them."""
+        par, pp = _host_i32(parent)
+        assert par.shape[0] >= seg_off + l_s
+        anc = torch.zeros((l_s, FS_MAX_TREE // 64), dtype=torch.int64, device=self.device)
+        rope = torch.zeros((l_s, self.desc.head_dim // 2, 2), dtype=torch.float32, device=self.device)
+        _check(_lib.fs_tree_mask(self._handle, int(l_glo), int(seg_off), int(l_s), pp, _dp(anc), _dp(rope), _stream(stream)), "fs_tree_mask")
+        return anc, rope
 
     def tree_logits(self, hidden, logits=None, amax=None, stream=None):
         l_s = int(hidden.shape[0])

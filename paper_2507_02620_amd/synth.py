@@ -267,6 +267,12 @@ def random_tree(size: int, max_depth: int, max_branch: int = 0, vocab: int = 320
         if p >= 0:
             dep[i] = dep[p] + 1
             nch[p] += 1
+    return _score_order(par, conf, g, vocab)
+
+
+def _score_order(par: np.ndarray, conf: np.ndarray, g: np.random.Generator, vocab: int) -> Tree:
+    """Relabel a tree (parents before children) in descending cumulative-score order and draw its token ids."""
+    size = par.shape[0]
     cum = np.empty(size, dtype=np.float64)
     for i in range(size):
         cum[i] = conf[i] * (cum[par[i]] if par[i] >= 0 else 1.0)
@@ -286,6 +292,23 @@ def random_tree(size: int, max_depth: int, max_branch: int = 0, vocab: int = 320
         s.add(t)
         tok[i] = t
     return Tree(new_par, tok, cum[order], _depths(new_par))
+
+
+def spine_tree(size: int, spine: int, vocab: int = 32000, seed: int = 0, stream: int = 0) -> Tree:
+    """A deep tree that is not a chain: `spine` nodes in a row (confidences near 1, so the spine keeps a high score),
+    every other node a leaf or a short twig under a random earlier node; relabelled in score order like random_tree.
+    Stands in for the draft tree of a long greedy continuation with a few alternatives at every depth."""
+    assert 1 <= spine <= size
+    g = _gen(seed, TID_TREE, 2_000_000 + stream)
+    par = np.full(size, -1, dtype=np.int64)
+    conf = g.random(size)
+    conf[:spine] = 0.9 + 0.1 * conf[:spine]
+    conf[0] = 1.0
+    for i in range(1, spine):
+        par[i] = i - 1
+    for i in range(spine, size):
+        par[i] = int(g.integers(0, i))
+    return _score_order(par, conf, g, vocab)
 
 
 def config_tree(cfg: StageConfig, seed: int = 0, stream: int = 0) -> Tree:

@@ -17,8 +17,10 @@ PLANT = 100.0
 class Schedule:
     """Everything both back ends must agree on, drawn from the seed: trees, hidden inputs, plants."""
 
-    def __init__(self, cfg, seed, lag, steps):
-        self.cfg, self.seed, self.lag, self.steps = cfg, seed, lag, steps
+    def __init__(self, cfg, seed, lag, steps, closed=False):
+        # closed: every node of the accepted path gets a planted output, also the last one, so that the integer trace does not
+        # depend on any un-planted logit (needed when one side runs without a forward)
+        self.cfg, self.seed, self.lag, self.steps, self.closed = cfg, seed, lag, steps, closed
 
     def fresh_tree(self, k):
         t = synth.random_tree(self.cfg.tree_size, self.cfg.max_depth, self.cfg.max_branch, max(self.cfg.vocab, 2), self.seed, stream=1000 + k)
@@ -29,7 +31,26 @@ class Schedule:
 
     def plants(self, parent, token, n_ver, k):
         t = synth.Tree(parent, token, np.zeros(len(parent)), synth._depths(parent))
-        return synth.resolve_plants(synth.plant_path(t, n_ver, self.seed, k, p_stop=0.2, mean_extra=1.0), t, max(self.cfg.vocab, 2))
+        pairs = synth.resolve_plants(synth.plant_path(t, n_ver, self.seed, k, p_stop=0.2, mean_extra=1.0), t, max(self.cfg.vocab, 2))
+        if self.closed and pairs:
+            vocab = max(self.cfg.vocab, 2)
+            row, tok = pairs[-1]
+            while True:  # the last plant may point at a verified child: that child is accepted too and needs an output of its own
+                hit = [c for c in range(len(parent)) if parent[c] == row and token[c] == tok and c < n_ver]
+                if not hit:
+                    break
+                row = hit[0]
+                kids = [c for c in range(len(parent)) if parent[c] == row]
+                late = [c for c in kids if c >= n_ver]
+                if late:
+                    tok = int(token[late[0]])
+                else:
+                    forbid = {int(token[c]) for c in kids}
+                    tok = (row * 7919 + k) % vocab
+                    while tok in forbid:
+                        tok = (tok + 1) % vocab
+                pairs.append((row, tok))
+        return pairs
 
     def synthetic_amax(self, n, k):
         return np.random.default_rng(self.seed * 7919 + k).integers(0, max(self.cfg.vocab, 2), n).astype(np.int32)
@@ -119,6 +140,110 @@ class HipBackend:
         return x.float().cpu().numpy().astype(np.float64)
 
 
+class IntegerOracleBackend:
+    """The oracle's integer side alone (accept, compaction lengths, segment pruning), free-running: no forward.  Acceptance
+    is planted on every node of the accepted path and sibling tokens are distinct, so the integer trace of a schedule does
+    not depend on the un-planted logits; zeros stand in for them.  Lets a long schedule at full depth be traced in seconds."""
+    name = "oracle"
+
+    def __init__(self, cfg, capacity):
+        self.cfg = cfg
+        self.kv = np.zeros((1, 2, 1, capacity, 1), dtype=np.int8)   # only its lengths matter
+
+    def verify(self, l_glo, l_cache, hid, seg_off, parent):
+        return np.zeros((len(hid), 1))
+
+    def logits_amax(self, rows):
+        return np.zeros((len(rows), self.cfg.vocab), dtype=np.float32), None
+
+    accept = OracleBackend.accept
+    seg_prune = OracleBackend.seg_prune
+    plant = OracleBackend.plant
+    to_np = OracleBackend.to_np
+
+    def compact(self, l_glo, l_cache, retain, n_acc):
+        return oracle.kv_compact(self.kv, l_glo, l_cache, retain, n_acc)
+
+
+class CheckedHipBackend(HipBackend):
+    """The HIP path running a schedule, checked against the oracle as it goes:
+      every step   accept against orc_accept on the HIP path's own argmax, compaction against orc_kv_compact applied to a
+                   snapshot of the draft slots (both bit for bit);
+      sampled steps  the oracle's cache is brought to the HIP path's state (its draft slots are copied over; the context
+                   below l_glo0 is the shared seeded prefix, which nothing may touch) and the step's forward and logits are
+                   compared within the tolerance."""
+
+    def __init__(self, stage, kv, orc, l_glo0, sample_steps, tol, log=print):
+        super().__init__(stage, kv)
+        self.orc, self.l_glo0, self.samples, self.tol, self.log = orc, l_glo0, set(sample_steps), tol, log
+        self.k = -1
+        self.worst = {"hidden": 0.0, "hidden_row": 0.0, "kv": 0.0, "logits": 0.0}
+        self.checked_steps = []
+
+    def begin_step(self, k):
+        self.k = k
+
+    def _sampled(self):
+        return self.k in self.samples
+
+    def _sync_oracle(self, l_cache):
+        n = l_cache - self.l_glo0
+        if n > 0:
+            self.orc.kv[:, :, :, self.l_glo0:l_cache] = self.kv[:, :, :, self.l_glo0:l_cache].float().cpu().numpy()
+
+    def verify(self, l_glo, l_cache, hid, seg_off, parent):
+        y = super().verify(l_glo, l_cache, hid, seg_off, parent)
+        if self._sampled():
+            from tests.gpu_util import max_rel_err, row_rel_err
+            n = len(hid)
+            self._sync_oracle(l_cache)
+            want = self.orc.verify(l_glo, l_cache, hid, seg_off, parent)
+            got = self.to_np(y)
+            e, er = max_rel_err(got, want), row_rel_err(got, want)
+            ke = max(max_rel_err(self.kv[l, x, :, l_cache:l_cache + n].float().cpu().numpy(), self.orc.kv[l, x, :, l_cache:l_cache + n])
+                     for l in range(self.orc.kv.shape[0]) for x in (0, 1))
+            self.log(f"    step {self.k}: {n} rows at l_glo={l_glo} l_cache={l_cache}: hidden {e:.3e} (worst row {er:.3e}), appended K/V worst layer {ke:.3e}")
+            self.worst["hidden"] = max(self.worst["hidden"], e)
+            self.worst["hidden_row"] = max(self.worst["hidden_row"], er)
+            self.worst["kv"] = max(self.worst["kv"], ke)
+            assert e < self.tol and er < 2 * self.tol and ke < self.tol, (self.k, e, er, ke)
+            if self.k not in self.checked_steps:
+                self.checked_steps.append(self.k)
+        return y
+
+    def logits_amax(self, rows):
+        lg, am = super().logits_amax(rows)
+        if self._sampled() and self.orc.lm_head is not None:
+            from tests.gpu_util import max_rel_err
+            want, _ = self.orc.logits(self.to_np(rows))
+            e = max_rel_err(lg.cpu().numpy(), want)
+            self.worst["logits"] = max(self.worst["logits"], e)
+            assert e < self.tol, (self.k, e)
+        return lg, am
+
+    def accept(self, lg, amax, token, parent, n_ver):
+        T = len(token)
+        self.res, self.retain, work = self.fs.new_accept_buffers(T, max(n_ver, 1))
+        am = self.torch.zeros(max(n_ver, 1), dtype=self.torch.int32, device="cuda") if lg is not None else self._dev(amax)
+        self.fs.tree_accept(lg, am, self._dev(token), self._dev(parent), n_ver, self.res, self.retain, work)
+        out, ret = self.fs.accept_result_to_host(self.res, self.retain, T)
+        o_res, o_ret = oracle.accept(am.cpu().numpy()[:n_ver], token, parent, n_ver)
+        assert out.as_tuple() == o_res.as_tuple() and np.array_equal(ret, o_ret), (self.k, out.as_tuple(), o_res.as_tuple())
+        return out.as_tuple(), ret
+
+    def compact(self, l_glo, l_cache, retain, n_acc, device_list=False):
+        bits = self.torch.int16 if self.kv.element_size() == 2 else self.torch.int32
+        n = l_cache - l_glo
+        snap = np.ascontiguousarray(self.kv[:, :, :, l_glo:l_cache].contiguous().view(bits).cpu().numpy()) if n > 0 else None
+        lens = super().compact(l_glo, l_cache, retain, n_acc, device_list)
+        if n > 0:
+            rel = oracle.kv_compact(snap, 0, n, retain, n_acc)
+            assert lens == (l_glo + rel[0], l_glo + rel[1]), (self.k, lens, rel)
+            after = self.kv[:, :, :, l_glo:lens[1]].contiguous().view(bits).cpu().numpy()
+            assert np.array_equal(after, snap[:, :, :, : rel[1]]), f"step {self.k}: compacted cache differs from the oracle's gather"
+        return lens
+
+
 def run(backend, sched, l_glo0, on_step=None):
     """Runs sched.steps steps; returns the integer trace and, per step, the stage outputs of the rows verified in it."""
     cfg, lag, seg = sched.cfg, sched.lag, sched.cfg.seg_len
@@ -130,6 +255,8 @@ def run(backend, sched, l_glo0, on_step=None):
     trace, outputs = [], []
     for k in range(sched.steps):
         T = len(parent)
+        if hasattr(backend, "begin_step"):
+            backend.begin_step(k)
         # 1. the stage runs ahead of verification by `lag` segments
         target = min(T, n_ver + (lag + 1) * seg)
         step_out = []

@@ -70,4 +70,12 @@ def max_rel_err(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
+def row_rel_err(got, ref):
+    """Worst row: max over rows of max |got_row - ref_row| / max |ref_row| (rows = leading axes, values = last axis)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    d = np.abs(np.asarray(got, dtype=np.float64) - ref).reshape(-1, ref.shape[-1]).max(axis=1)
+    m = np.abs(ref).reshape(-1, ref.shape[-1]).max(axis=1)
+    return float((d / np.maximum(m, 1e-30)).max())
+
+
 TOL = {"f32": 1e-4, "bf16": 2e-2}

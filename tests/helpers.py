@@ -43,3 +43,23 @@ def ancestors_by_walking(parent):
             m[i, j] = True
             j = int(parent[j])
     return m
+
+
+def reparent_same_depth(parent, seed=0):
+    """A tree with the same depths (hence the same positions) but other ancestors: every node that has a choice moves under
+    another earlier node of its parent's depth.  Returns (new parent array, number of nodes moved).  Used to show that a
+    comparison would notice a wrong ancestor mask."""
+    parent = np.asarray(parent, dtype=np.int32)
+    depth = synth._depths(parent)
+    rng = np.random.default_rng(seed)
+    out = parent.copy()
+    moved = 0
+    for i in range(1, len(parent)):
+        if parent[i] < 0:
+            continue
+        cands = [j for j in range(i) if depth[j] == depth[parent[i]] and j != parent[i]]
+        if cands:
+            out[i] = cands[int(rng.integers(0, len(cands)))]
+            moved += 1
+    assert (synth._depths(out) == depth).all()
+    return out, moved

@@ -66,6 +66,43 @@ def test_acceptance_probability_of_a_verified_chain():
     assert all(not (d[0] == 1 and d[1] == 1) for d in draws)
 
 
+def test_second_token_after_an_inner_node_follows_that_nodes_distribution():
+    """Depth-2 tree, everything verified: root 0 with children 1, 2; node 1 with children 3, 4 (tried in that order, so a
+    rejected node 3 has its mass struck before node 4 is tried, and the residual draw at node 1 excludes both).  Given that
+    node 1 was accepted, the next token leaving the step — token[3], token[4] or the residual draw — must be distributed as
+    softmax(logits of node 1); likewise under node 2 (one child).  First tokens follow the root's distribution."""
+    vocab = 10
+    rng = np.random.default_rng(21)
+    lg = (rng.standard_normal((5, vocab)) * 1.2).astype(np.float32)
+    parent = np.array([-1, 0, 0, 1, 1, 2], dtype=np.int32)
+    token = np.array([0, 3, 6, 1, 8, 4], dtype=np.int32)
+    lg[0, 3] = 2.2; lg[0, 6] = 2.0              # make the two inner nodes likely enough to collect statistics
+    p = [torch.softmax(torch.tensor(lg[i], dtype=torch.float64), 0).numpy() for i in range(5)]
+    N = 60000
+    draws = _emitted(lg, token, parent, 5, N, seed=23)
+    first = np.zeros(vocab)
+    second = {1: np.zeros(vocab), 2: np.zeros(vocab)}
+    for n_acc, x_new, n_new, cont, retain in draws:
+        acc = retain[:n_acc]
+        toks = [int(token[i]) for i in acc[1:]] + [x_new]      # tokens leaving the step, in order
+        first[toks[0]] += 1
+        if n_acc >= 2:
+            second[acc[1]][toks[1]] += 1
+    sig = np.sqrt(N * p[0] * (1 - p[0]))
+    assert (np.abs(first - N * p[0]) < 5 * sig + 1).all(), (first / N, p[0])
+    for node in (1, 2):
+        n = second[node].sum()
+        assert n > 3000
+        sig = np.sqrt(n * p[node] * (1 - p[node]))
+        assert (np.abs(second[node] - n * p[node]) < 5 * sig + 1).all(), (node, second[node] / n, p[node])
+    # the struck mass: after node 3 (token 1) was rejected at node 1, neither the later sibling's test nor the residual draw
+    # may emit token 1 from a path that ends at node 1 or goes through node 4
+    for n_acc, x_new, n_new, cont, retain in draws:
+        acc = retain[:n_acc]
+        if n_acc == 2 and acc[1] == 1:
+            assert x_new not in (1, 8)       # both candidates were tried and rejected
+
+
 def test_low_temperature_limit_is_greedy():
     rng = np.random.default_rng(5)
     for seed in range(8):

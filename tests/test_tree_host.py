@@ -142,7 +142,8 @@ def test_error_codes():
 
 
 def test_timing_at_the_papers_tree_sizes(capsys):
-    """Not a gate: prints the host cost per call at L0 = 80 / L_exp = 64 so that it can be quoted beside the GPU numbers."""
+    """Prints the host cost per call at L0 = 80 / L_exp = 64 so that it can be quoted beside the GPU numbers (no time limit
+    is asserted: the box may be busy)."""
     fs = _fs()
     parent, token, conf = _random_base(400, 32000, 9)
     t0 = time.perf_counter()
@@ -156,4 +157,4 @@ def test_timing_at_the_papers_tree_sizes(capsys):
         fs.tree_merge(par, tok, new.parent, tnew)
     t_mrg = (time.perf_counter() - t0) / 200
     print(f"fs_tree_segment(400 -> 80): {t_seg * 1e6:.1f} us; fs_tree_merge(80 + 64): {t_mrg * 1e6:.1f} us (incl. ctypes marshalling)")
-    assert t_seg < 5e-3 and t_mrg < 5e-3
+    assert t_seg > 0 and t_mrg > 0
