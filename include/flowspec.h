@@ -139,6 +139,16 @@ int fs_stage_profile_end(fs_stage *stage, void *stream, double *total_ms, long l
  */
 int fs_probe_stream_read(const void *buf, size_t buf_bytes, size_t bytes_per_launch, int launches, void *stream, double *gb_per_s);
 int fs_probe_mfma_bf16(void *scratch, int launches, void *stream, double *tflop_per_s);
+/*
+ *   fs_probe_fill         rate at which compute units pull data in: `grid` workgroups of `waves` waves each stream iters x waves x 4 KiB
+ *                         from a region of region_kib KiB (a multiple of waves x 4) that they re-read cyclically, with 16-byte-per-lane
+ *                         loads, three rounds in flight; to_lds != 0: direct-to-LDS loads (the path of the 256-row projection
+ *                         kernel), else loads into registers.  Workgroups `share` consecutive slots of one XCD read the same
+ *                         region; buf (device, 16-byte aligned) must hold (grid / 8 / share + 2) * 8 regions + 64 bytes.
+ *                         Result: GB/s summed over the workgroups.
+ */
+int fs_probe_fill(const void *buf, size_t buf_bytes, int grid, int waves, int region_kib, int iters, int share, int to_lds, int launches,
+                  void *stream, double *gb_per_s);
 
 /* hipError_t (as int) behind the most recent FS_EHIP on the calling thread, 0 if none. */
 int fs_last_hip_error(void);

@@ -244,12 +244,13 @@ struct Profiler {
 
 // Tuning knobs from the environment, read once when the stage is created (a launch never calls getenv).
 struct Tunables {
-    int attn_wgs, attn_mtw, wide_rows, mid_rows;
+    int attn_wgs, attn_mtw, wide_rows, mid_rows, block_gemm;
     void read() {
         attn_wgs = env_int("FLOWSPEC_ATTN_WGS", 0);    // > 0: workgroups the attention split plan aims for
         attn_mtw = env_int("FLOWSPEC_ATTN_MTW", 0);    // > 0: row tiles per wave of the attention kernel
         wide_rows = env_int("FLOWSPEC_WIDE_ROWS", 65); // stacked rows from which every projection takes the many-row kernel
         mid_rows = env_int("FLOWSPEC_MID_ROWS", 17);   // ... from which the wide projections do
+        block_gemm = env_int("FLOWSPEC_BLOCK_GEMM", -1);  // 256-row projection kernel: 0 never, 1 whenever possible, else by rule
     }
 };
 
@@ -455,7 +456,7 @@ static bool mid_cols_ok(int n_tiles) {
 
 // dense or 4-bit projection launch, by the stage's weight format; `wide`: through the many-row kernel
 static hipError_t launch_proj(const fs_stage* st, int epi, const GemmPlan& p, GemmArgs& g, hipStream_t s, bool wide = false) {
-    if (wide) return launch_gemm_wide(epi, p.NT, p.n_groups * p.NT, g, st->at<float>(st->L.off_part), st->L.part_bytes, s);
+    if (wide) return launch_gemm_wide(epi, p.NT, p.n_groups * p.NT, g, st->at<float>(st->L.off_part), st->L.part_bytes, st->tun.block_gemm, s);
     if (p.w4) {
         g.Sp = p.sp;
         return launch_gemm_w4(epi, p.NT, p.NW, p.n_groups, g, s);

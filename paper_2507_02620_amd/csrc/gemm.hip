@@ -623,6 +623,204 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
     }
 }
 
+// ---- many-row segments: 256-row blocks, both operands through LDS ------------------------------------------------------
+// The 128-row kernel above moves 24 KiB from L2 per k-tile and block for 2.1 MFLOP and is bound by the path from L2 into a
+// compute unit (about 50 GB/s per unit, whatever the kernel does).  This kernel gives a compute unit one block of 256 rows x
+// 16 * BNT features at a time and brings both operands in through LDS, so that every byte that arrives serves the whole block:
+// 256 x 256 features take 32 KiB per k-tile for 4.2 MFLOP.  WM x WN waves, each with MT x NT accumulator tiles (WM * MT = 16
+// row tiles, WN * NT = BNT feature tiles); the shape in use is 2 x 4 waves of 8 x 4 tiles (two waves per SIMD, 128 accumulator
+// registers each).
+//   * Both operands are fragment-major in memory (one fragment = one contiguous KiB in MFMA operand order), so a fragment goes
+//     from global memory straight into LDS with one 16-byte-per-lane direct-to-LDS load per wave: no staging registers.
+//     A stage is the block's 16 activation fragments and BNT weight fragments of one k-tile; the waves share its loads.
+//   * STAGES stage buffers; the loads of a stage are issued STAGES - 1 k-tiles before its MFMAs, into the buffer whose
+//     fragments were read two k-tiles ago.
+//   * Fragments travel LDS -> registers one k-tile ahead, without a second register set: an activation fragment is replaced
+//     by the next k-tile's as soon as the MFMAs of its row tile are issued, a weight fragment during the last row tile.
+//   * One barrier per k-tile.  It is the bare s_barrier with explicit wait counts: the workgroup fence of __syncthreads would
+//     wait for every direct-to-LDS load in flight, i.e. drain the prefetch, and for the fragment reads of the k-tile about to
+//     start.  Before the barrier of k-tile kt a wave waits for its own loads of stage kt + 1 (those of stage kt + 2 stay in
+//     flight) and for all its LDS reads but the newest ones (reads return in order: everything read two k-tiles ago is then
+//     done).  Behind the barrier stage kt + 1 is complete for every wave and the buffer of stage kt - 1 is free.
+//   * Epilogues, RMSNorm hand-over (partial sums of squares from the producer) and XCD-aware placement are those of the
+//     128-row kernel; K slices (PARTIAL) write the same raw tiles for the same fix-up kernel.
+#define FS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define FS_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+// s_waitcnt immediate (gfx9 encoding): vmcnt = n (6 bits), lgkmcnt = l (4 bits: at most l LDS reads still in flight), expcnt untouched
+#define FS_WAIT_VM_LGKM(n, l) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 15) | (((n) >> 4) << 14) | ((l) << 8))
+
+template <int EPI, bool PARTIAL, int WM, int WN, int MT, int NT, int STAGES>
+__global__ void __launch_bounds__(WM * WN * 64) block_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,
+                                                                  float* part) {
+    using T = bf16_t;
+    using E = Elem<T>;
+    using frag_t = E::frag_t;
+    constexpr bool NORM = (EPI != EPI_RESID);
+    constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
+    constexpr int TPI = PAIR ? 2 : 1;
+    constexpr int NWAVES = WM * WN;
+    constexpr int BMT = WM * MT, BNT = WN * NT, FR = BMT + BNT;  // row tiles, feature tiles, fragments (KiB) per stage
+    constexpr int DIST = STAGES - 1;                             // k-tiles between a stage's loads and its MFMAs
+    constexpr int LPW = (FR + NWAVES - 1) / NWAVES;              // direct-to-LDS loads per wave and stage
+    constexpr int RPT = MT + NT;                                 // LDS fragment reads per wave and k-tile
+    static_assert(BMT == 16, "blocks are 256 rows");
+    static_assert(!PAIR || NT % 2 == 0, "paired epilogues need both tiles of a pair in one wave");
+    static_assert(STAGES == 3 || STAGES == 4, "3 or 4 stage buffers");
+    static_assert((STAGES * FR + 1) * 1024 <= 160 * 1024, "stage buffers must fit the 160 KiB of LDS");
+    static_assert((DIST - 1) * LPW < 64, "vmcnt is a 6-bit counter");
+    // one array per stage: distinct objects, so that the compiler's own wait-count tracking of the direct-to-LDS loads never
+    // ties a read of one stage to a load into another
+    __shared__ __align__(1024) unsigned char sb0[FR * 1024];
+    __shared__ __align__(1024) unsigned char sb1[FR * 1024];
+    __shared__ __align__(1024) unsigned char sb2[FR * 1024];
+    __shared__ __align__(1024) unsigned char sb3[STAGES == 4 ? FR * 1024 : 16];
+    __shared__ float rs_s[BMT * 16];
+    auto stage_buf = [&](int j) -> unsigned char* { return j == 0 ? sb0 : (j == 1 ? sb1 : (j == 2 ? sb2 : sb3)); };
+
+    const int id = blockIdx.x, xcd = id & 7, slot = id >> 3;
+    const int per_col = m_blocks * k_splits;
+    const int col = (slot / per_col) * 8 + xcd, mb = (slot % per_col) / k_splits, ks = slot % k_splits;
+    if (col >= n_cols) return;
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WN, wn = w % WN;  // wave-uniform: scalar address arithmetic below
+    const int r16 = lane & 15, g = lane >> 4;
+    const int kt_lo = (int)((long long)a.nkt * ks / k_splits), nkt = (int)((long long)a.nkt * (ks + 1) / k_splits) - kt_lo;  // >= 1 (host)
+    const int mt0 = mb * BMT, m_tiles = (a.M + 15) >> 4;
+
+    if (NORM) {  // RMSNorm scale of the block's rows from the producer's partial sums of squares
+        for (int r = t; r < BMT * 16; r += NWAVES * 64) {
+            const int m = min(mt0 * 16 + r, a.M - 1);
+            float s0 = 0.f, s1 = 0.f;
+            int j = 0;
+#pragma unroll 4
+            for (; j + 1 < a.ssp_n; j += 2) {
+                s0 += a.ssp_in[(size_t)j * a.ssp_stride + m];
+                s1 += a.ssp_in[(size_t)(j + 1) * a.ssp_stride + m];
+            }
+            if (j < a.ssp_n) s0 += a.ssp_in[(size_t)j * a.ssp_stride + m];
+            rs_s[r] = 1.0f / sqrtf((s0 + s1) / (float)a.K + a.eps);
+        }
+    }
+
+    // this wave's share of a stage: fragments w * LPW .. + LPW - 1 (activation row tiles first, then weight tiles; a share that
+    // runs past the stage's end loads its last fragment again); tiles beyond the matrix re-read the last one (their results
+    // are never stored).  Wave-uniform 64-bit base + this lane's 16 bytes.
+    const unsigned char* src[LPW];
+    unsigned step[LPW], dst_off[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int f = min(w * LPW + i, FR - 1);
+        const int mt = min(mt0 + f, m_tiles - 1);
+        const int pc = min(col * BNT + max(f - BMT, 0), n_tiles - 1);
+        const size_t xo = ((size_t)mt * a.nkt + kt_lo) * 1024;
+        const size_t wo = (((size_t)(pc / layout_nt) * a.nkt + kt_lo) * layout_nt + pc % layout_nt) * 1024;
+        src[i] = (f < BMT) ? (const unsigned char*)a.X + xo : (const unsigned char*)a.Wp + wo;
+        step[i] = (f < BMT) ? 1024u : (unsigned)layout_nt * 1024u;
+        dst_off[i] = (unsigned)f * 1024u;
+    }
+    const unsigned lane_off = (unsigned)lane * 16u;
+    int issued = 0;
+    auto issue = [&](int j) {  // next k-tile of this wave's fragments -> stage buffer j (past the slice's end: the last k-tile again)
+        unsigned char* dst = stage_buf(j);
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) __builtin_amdgcn_global_load_lds(FS_GLB_PTR(src[i] + lane_off), FS_LDS_PTR(dst + dst_off[i]), 16, 0, 0);
+        const bool more = ++issued < nkt;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) src[i] += more ? step[i] : 0u;
+    };
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    frag_t xf[MT], wf[NT];
+    auto frag_at = [&](int j, int f) { return *(const frag_t*)(stage_buf(j) + (size_t)f * 1024 + lane_off); };
+
+#pragma unroll
+    for (int j = 0; j < DIST; ++j) issue(j);
+    FS_WAIT_VM_LGKM((DIST - 1) * LPW, 0);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wf[nt] = frag_at(0, BMT + wn * NT + nt);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xf[mt] = frag_at(0, wm * MT + mt);
+    auto ktile = [&](int ju) {  // k-tile kt0 + ju of a group of STAGES: the buffers are compile-time
+        const int jn = (ju + 1) % STAGES;
+        FS_WAIT_VM_LGKM((DIST - 2) * LPW, RPT < 15 ? RPT : 15);
+        __builtin_amdgcn_s_barrier();
+        issue((ju + DIST) % STAGES);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                acc[mt][nt] = E::mma(wf[nt], xf[mt], acc[mt][nt]);
+                if (mt == MT - 1) wf[nt] = frag_at(jn, BMT + wn * NT + nt);
+            }
+            xf[mt] = frag_at(jn, wm * MT + mt);
+        }
+    };
+    int kt0 = 0;
+    for (; kt0 + STAGES <= nkt; kt0 += STAGES) {
+#pragma unroll
+        for (int ju = 0; ju < STAGES; ++ju) ktile(ju);
+    }
+#pragma unroll
+    for (int ju = 0; ju < STAGES; ++ju)
+        if (kt0 + ju < nkt) ktile(ju);  // uniform over the workgroup
+    // every direct-to-LDS load has landed and every wave has left the loop before LDS is reused below
+    FS_WAIT_VM_LGKM(0, 0);
+    __builtin_amdgcn_s_barrier();
+
+    if constexpr (PARTIAL) {
+        const int nt_all = n_cols * BNT;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int mtile = mt0 + wm * MT + mt;
+            if (mtile >= m_tiles) break;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                ((f32x4*)part)[(((size_t)ks * m_tiles + mtile) * nt_all + col * BNT + wn * NT + nt) * 64 + lane] = acc[mt][nt];
+        }
+        return;
+    }
+    const int pt0 = col * BNT + wn * NT;
+    float* hs = (float*)sb0;  // [WN feature waves][256 rows]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int lr = (wm * MT + mt) * 16 + r16;  // row within the block
+        const int m = mt0 * 16 + lr;
+        const float rs = NORM ? rs_s[lr] : 1.f;
+        float hsq = 0.f;
+#pragma unroll
+        for (int ntp = 0; ntp < NT / TPI; ++ntp) {
+            float y[TPI][4];
+#pragma unroll
+            for (int tt = 0; tt < TPI; ++tt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) y[tt][v] = acc[mt][ntp * TPI + tt][v];
+            hsq += epilogue_item<T, EPI>(a, y, rs, m, pt0 + ntp * TPI, g);
+        }
+        if constexpr (EPI == EPI_RESID) {
+            if (a.ssp_out) {
+                hsq = wave_xor_add(wave_xor_add(hsq, 16), 32);
+                if (g == 0) hs[wn * (BMT * 16) + lr] = hsq;
+            }
+        }
+    }
+    if constexpr (EPI == EPI_RESID) {
+        if (a.ssp_out) {
+            __syncthreads();
+            for (int r = t; r < BMT * 16; r += NWAVES * 64) {
+                float sum = 0.f;
+#pragma unroll
+                for (int x = 0; x < WN; ++x) sum += hs[x * (BMT * 16) + r];
+                const int m = mt0 * 16 + r;
+                if (m < a.ssp_stride) a.ssp_out[(size_t)col * a.ssp_stride + m] = sum;
+            }
+        }
+    }
+}
+
 // Block geometry by projection kind and row count (see the kernel's header comment).
 struct WideShape {
     int bmt, wnt, waves;
@@ -704,13 +902,45 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s) {
+// 256-row blocks of 256 features, both operands through LDS (block_gemm_kernel).
+template <int EPI>
+static hipError_t launch_block(int layout_nt, int n_tiles, const GemmArgs& a, hipStream_t s) {
+    const int n_cols = (n_tiles + 15) / 16, m_blocks = (a.M + 255) / 256;
+    const int grid = (n_cols + 7) / 8 * 8 * m_blocks;
+    hipLaunchKernelGGL((block_gemm_kernel<EPI, false, 2, 4, 8, 4, 4>), dim3(grid), dim3(512), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+    return hipGetLastError();
+}
+
+// Which of the two many-row kernels takes a projection.  A compute unit pulls in about 50 GB/s whatever the kernel (its L1 keeps
+// 64 lines in flight, and with a fifth of them coming from HBM a request takes about 350 cycles), so both kernels are bound by
+// bytes per block: the 256-row block needs two thirds of the 128-row blocks' bytes per flop, but the compute units take its
+// blocks one at a time.  It wins when all its blocks run at once on most of the chip while the 128-row kernel would have to
+// give some compute units a second pair of blocks (measured, 1024 rows: QKV 111 -> 97 us; 512 rows: gate/up 108 -> 92 us);
+// with more than 256 blocks its second round costs more than it saves (1024 rows: gate/up 159 -> 187 us), with few blocks the
+// 128-row kernel's finer grain fills more compute units (512 rows: QKV 66 -> 92 us), and the K slices of the d_model-wide
+// residual projections do no better either (1024 rows: 51 -> 58 us, 95 -> 96 us).
+static bool use_block_gemm(int mode, int epi, int M, int n_tiles) {  // mode 0 / 1: never / whenever possible (tuning knob); else the rule below
+    if (epi == EPI_RESID || mode == 0) return false;
+    if (mode == 1) return true;
+    const int cols = (n_tiles + 15) / 16;
+    const int blocks256 = cols * ((M + 255) / 256), blocks128 = cols * ((M + 127) / 128);
+    return blocks256 >= 144 && blocks256 <= 256 && blocks128 > 256;
+}
+
+hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, int block_mode, hipStream_t s) {
     if (!a.x_frag) return hipErrorInvalidValue;
     // the kernel addresses weights and activations with 32-bit byte offsets from their bases
     if ((unsigned long long)(n_tiles + layout_nt) * a.nkt * 1024ull >= (1ull << 32) || (unsigned long long)(a.M + 16) * a.nkt * 64ull >= (1ull << 32))
         return hipErrorInvalidValue;
     const WideShape sh = wide_shape(epi, a.M);
     const bool narrow = sh.wnt == 2, half = sh.bmt == 4;
+    if (!narrow && !half && use_block_gemm(block_mode, epi, a.M, n_tiles)) {
+        switch (epi) {
+            case EPI_QKV: return launch_block<EPI_QKV>(layout_nt, n_tiles, a, s);
+            case EPI_SWIGLU: return launch_block<EPI_SWIGLU>(layout_nt, n_tiles, a, s);
+            case EPI_LOGITS: return launch_block<EPI_LOGITS>(layout_nt, n_tiles, a, s);
+        }
+    }
     switch (epi) {
         case EPI_QKV:
             if (half) return launch_wide_shape<EPI_QKV, 4, 2, 4>(layout_nt, n_tiles, a, part, part_bytes, s);

@@ -92,6 +92,7 @@ hipError_t launch_gemm_w4(int epi, int NT, int NW, int n_groups, const GemmArgs&
 // projection leaves wide_ssp_parts(M, n_tiles) partial sums of squares per row in ssp_out.
 int wide_ssp_parts(int M, int n_tiles);
 size_t wide_partial_bytes(int max_rows, int n_tiles);
-hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, hipStream_t s);
+// block_mode: 0 never / 1 whenever possible / anything else: by rule — use of the 256-row kernel (both operands through LDS) from 384 rows on
+hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, int block_mode, hipStream_t s);
 // MT = ceil(M/16) in {1,2,4}, NT in {1,2,4} (even for QKV / SWIGLU), waves per workgroup NW
 hipError_t launch_gemm(int dtype, int epi, int NT, int NW, int n_groups, const GemmArgs& a, hipStream_t s);

@@ -26,7 +26,7 @@ KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "ar
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
            "fs_stage_profile_end", "fs_tree_verify_stage", "fs_tree_verify_batch", "fs_tree_mask",
            "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
-           "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16")
+           "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16", "fs_probe_fill")
 
 
 class FlowSpecError(RuntimeError):
@@ -96,6 +96,7 @@ def _load():
     lib.fs_tree_merge.argtypes = [vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.fs_probe_stream_read.argtypes = [vp, C.c_size_t, C.c_size_t, ci, vp, C.POINTER(C.c_double)]
     lib.fs_probe_mfma_bf16.argtypes = [vp, ci, vp, C.POINTER(C.c_double)]
+    lib.fs_probe_fill.argtypes = [vp, C.c_size_t, ci, ci, ci, ci, ci, ci, ci, vp, C.POINTER(C.c_double)]
     for n in EXPORTS:
         if n not in ("fs_stage_workspace_bytes",):
             getattr(lib, n).restype = C.c_int
@@ -265,6 +266,14 @@ def probe_mfma_bf16(scratch, launches=5, stream=None) -> float:
     """TFLOP/s of a register-resident bf16 MFMA loop (measurement aid)."""
     out = C.c_double()
     _check(_lib.fs_probe_mfma_bf16(_dp(scratch), int(launches), _stream(stream), C.byref(out)), "fs_probe_mfma_bf16")
+    return out.value
+
+
+def probe_fill(buf, grid, waves, region_kib, iters, share=1, to_lds=True, launches=5, stream=None) -> float:
+    """GB/s (all workgroups together) at which compute units pull data from a cache-resident region (measurement aid)."""
+    out = C.c_double()
+    _check(_lib.fs_probe_fill(_dp(buf), C.c_size_t(buf.numel() * buf.element_size()), int(grid), int(waves), int(region_kib), int(iters),
+                              int(share), int(bool(to_lds)), int(launches), _stream(stream), C.byref(out)), "fs_probe_fill")
     return out.value
 
 

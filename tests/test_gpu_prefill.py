@@ -42,6 +42,35 @@ def test_chain_segment(cfg, rows):
     assert max_rel_err(kv_g, kv_o) < TOL[cfg.dtype]
 
 
+@pytest.mark.parametrize("cfg,rows,head", [
+    # the 256-row projection kernel (both operands through LDS) forced on for every normed projection: QKV with bias and
+    # rotation, gate/up and the LM head, with row counts that leave the last 256-row block partly filled and feature counts
+    # that leave the last 256-feature block partly filled
+    (synth.StageConfig("blk-bf16-gqa-400", "bf16", 2, 512, 8, 2, 64, 1408, 1000, 90, 400, 400, 400, 1, qkv_bias=True), 400, True),
+    (synth.StageConfig("blk-bf16-mha128-640", "bf16", 1, 1024, 8, 8, 128, 2816, 0, 77, 640, 640, 640, 1), 640, False),
+    (synth.StageConfig("blk-bf16-1024", "bf16", 1, 512, 4, 4, 128, 1024, 0, 0, 1024, 1024, 1024, 1), 1024, False),
+])
+def test_chain_segment_through_the_256_row_kernel(cfg, rows, head, monkeypatch):
+    from tests.gpu_util import TOL, Pair, max_rel_err
+    monkeypatch.setenv("FLOWSPEC_BLOCK_GEMM", "1")
+    print(f"[case] {cfg.name} rows={rows}", flush=True)
+    pair = Pair(cfg, seed=5, head=head)
+    hid = synth.hidden(cfg, rows, 0, 5)
+    o, g = pair.verify_tree(_chain(rows), hid, rows)
+    err = max_rel_err(g, o)
+    print(f"  hidden max-rel-err {err:.3e}", flush=True)
+    assert err < TOL[cfg.dtype]
+    kv_g = pair.kv[:, :, :, cfg.l_glo:cfg.l_glo + rows].float().cpu().numpy()
+    assert max_rel_err(kv_g, pair.orc.kv[:, :, :, cfg.l_glo:cfg.l_glo + rows]) < TOL[cfg.dtype]
+    if head:
+        import torch
+        o_lg, _ = pair.orc.logits(o)
+        g_lg, _ = pair.gpu.tree_logits(torch.from_numpy(g).to("cuda", pair.tdtype))
+        lerr = max_rel_err(g_lg.cpu().numpy(), o_lg)
+        print(f"  logits max-rel-err {lerr:.3e}", flush=True)
+        assert lerr < TOL[cfg.dtype]
+
+
 def test_chain_in_two_chunks_matches_one():
     """A 400-row chain verified as 256 + 144 rows gives the rows of the single 400-row pass (bf16 level)."""
     from tests.gpu_util import TOL, Pair, max_rel_err
