@@ -236,6 +236,18 @@ int fs_tree_accept(const float *logits, int32_t *amax, int vocab, const int32_t 
                    fs_accept_result *res, int32_t *retain, int32_t *work, void *stream);
 
 /*
+ * fs_tree_accept for callers that cannot allocate device memory or carry a scratch buffer around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as fs_tree_accept without
+ * `work`: the partial maxima of the row argmax live in a static device array inside the library (512 KiB per GPU, held
+ * until the process ends; sized for n_ver <= FS_MAX_TREE rows and any vocab).  Calls no hipMalloc / hipFree or other
+ * allocating routine.  All calls on one GPU share that array: calls that overlap in time on one GPU (different streams
+ * or threads) race on it; calls on one stream do not.  Nothing in it needs clearing between calls.
+ * Errors: FS_EINVAL, FS_ECAP (T > FS_MAX_TREE: beyond what the static array is sized for), FS_EHIP.
+ */
+int fs_tree_accept_noalloc(const float *logits, int32_t *amax, int vocab, const int32_t *token, const int32_t *parent, int T, int n_ver,
+                           fs_accept_result *res, int32_t *retain, void *stream);
+
+/*
  * Stochastic acceptance at a temperature > 0 (the paper's temperature-1 runs, Table I; Sec. III-C gives no formula).
  * Reading taken: sequential candidate test.  At an accepted node u with p = softmax(logits_u / temperature) the children of
  * u are tried in S order; a child is accepted with probability p(token) / (mass not yet rejected at u); a rejected token's

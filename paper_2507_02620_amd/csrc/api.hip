@@ -2,6 +2,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <algorithm>
 #include <vector>
@@ -264,6 +265,34 @@ struct fs_stage {
     template <typename P>
     P* at(size_t off) const { return (P*)(ws + off); }
 };
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------------------------
+// fs_tree_accept_noalloc keeps the per-chunk partial maxima of the row argmax (what fs_tree_accept takes as `work`) in a
+// file-scope device array: 2 int32 (value bits, index) per row and chunk, FS_MAX_TREE rows at most, 512 KiB on every GPU
+// the library runs on, held until the process ends.  The array's name is only a handle on the host: the device address
+// is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) int32_t noalloc_scratch_mem[2 * FS_MAX_TREE * FS_ARGMAX_CHUNKS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+int noalloc_scratch(int32_t** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(noalloc_scratch_mem)));
+        if (!p) return FS_EHIP;
+        g_scratch_ptr[dev] = (int32_t*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FS_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -690,6 +719,24 @@ int fs_tree_accept(const float* logits, int32_t* amax, int vocab, const int32_t*
         HIP_TRY(launch_argmax(logits, n_ver, vocab, FS_ARGMAX_CHUNKS, work, amax, s));
     }
     static_assert(sizeof(fs_accept_result) == sizeof(AcceptResultDev), "result layouts must agree");
+    HIP_TRY(launch_accept(amax, token, parent, T, n_ver, (AcceptResultDev*)res, retain, s));
+    return FS_OK;
+}
+
+int fs_tree_accept_noalloc(const float* logits, int32_t* amax, int vocab, const int32_t* token, const int32_t* parent, int T, int n_ver,
+                           fs_accept_result* res, int32_t* retain, void* stream) {
+    if (!token || !parent || !res || !retain || T < 1 || n_ver < 0 || n_ver > T) return FS_EINVAL;
+    if (T > FS_MAX_TREE) return FS_ECAP;  // the static scratch holds the partial maxima of at most FS_MAX_TREE rows
+    if (n_ver > 0 && !amax) return FS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (logits && n_ver > 0) {
+        if (vocab < 1) return FS_EINVAL;
+        int32_t* work = nullptr;
+        const int rc = noalloc_scratch(&work);
+        if (rc) return rc;
+        // every (row, chunk) entry the second argmax pass reads is written by the first: nothing has to start at zero
+        HIP_TRY(launch_argmax(logits, n_ver, vocab, FS_ARGMAX_CHUNKS, work, amax, s));
+    }
     HIP_TRY(launch_accept(amax, token, parent, T, n_ver, (AcceptResultDev*)res, retain, s));
     return FS_OK;
 }

@@ -25,7 +25,7 @@ KERNEL_KINDS = ("prepare", "qkv", "attn", "oproj", "gateup", "down", "head", "ar
 
 EXPORTS = ("fs_stage_workspace_bytes", "fs_stage_create", "fs_stage_destroy", "fs_last_hip_error", "fs_stage_profile_begin",
            "fs_stage_profile_end", "fs_tree_verify_stage", "fs_tree_verify_batch", "fs_tree_mask",
-           "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
+           "fs_tree_logits", "fs_tree_accept", "fs_tree_accept_noalloc", "fs_tree_accept_sample", "fs_accept_result_to_host", "fs_kv_compact", "fs_seg_prune", "fs_tree_segment",
            "fs_tree_prune", "fs_tree_merge", "fs_probe_stream_read", "fs_probe_mfma_bf16", "fs_probe_fill")
 
 
@@ -87,6 +87,7 @@ def _load():
     lib.fs_tree_logits.argtypes = [vp, vp, ci, vp, vp, vp]
     lib.fs_tree_mask.argtypes = [vp, ci, ci, ci, i32p, vp, vp, vp]
     lib.fs_tree_accept.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, vp]
+    lib.fs_tree_accept_noalloc.argtypes = [vp, vp, ci, vp, vp, ci, ci, vp, vp, vp]
     lib.fs_tree_accept_sample.argtypes = [vp, ci, C.c_float, vp, vp, ci, ci, C.c_uint64, C.c_uint64, vp, vp, vp, vp]
     lib.fs_accept_result_to_host.argtypes = [vp, vp, ci, C.POINTER(AcceptResult), i32p, vp]
     lib.fs_kv_compact.argtypes = [vp, KVCache, ci, ci, vp, vp, ci, ci, vp, vp]
@@ -282,6 +283,14 @@ def tree_accept(logits, amax, token, parent, n_ver, res, retain, work=None, stre
     vocab = int(logits.shape[1]) if logits is not None else 0
     _check(_lib.fs_tree_accept(_dp(logits), _dp(amax), vocab, _dp(token), _dp(parent), T, int(n_ver), _dp(res), _dp(retain), _dp(work),
                                _stream(stream)), "fs_tree_accept")
+
+
+def tree_accept_noalloc(logits, amax, token, parent, n_ver, res, retain, stream=None):
+    """tree_accept without a caller-provided scratch buffer (the library's static device array takes its place)."""
+    T = int(token.shape[0])
+    vocab = int(logits.shape[1]) if logits is not None else 0
+    _check(_lib.fs_tree_accept_noalloc(_dp(logits), _dp(amax), vocab, _dp(token), _dp(parent), T, int(n_ver), _dp(res), _dp(retain),
+                                       _stream(stream)), "fs_tree_accept_noalloc")
 
 
 def tree_accept_sample(logits, temperature, token, parent, n_ver, seed, step, res, retain, work=None, stream=None):
