@@ -26,28 +26,33 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+GEMM_SRC = "paper_2507_02620_amd/csrc/gemm.hip"
 
 
-def read_traffic(path):
-    """HBM bytes per launch of the dominant kernel from a committed rocprofv3 --pmc summary ('traffic_bytes: N'), or None."""
+def source_sha(rel):
+    """sha256 (first 16 hex digits) of a source file of the library, the stamp the counter summaries under profiles/ carry."""
+    import hashlib
+    try:
+        return hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+
+
+def read_traffic(path, source_rel):
+    """(HBM bytes per launch, stale) of the dominant kernel from a committed rocprofv3 --pmc summary: the file holds a line
+    'traffic_bytes: N' and a line 'kernel_source_sha256: H' with the stamp of the kernel's source file at the time the counters
+    were taken.  stale = the source has changed since (or the file has no stamp): the figure is then context, not evidence.
+    Counters cannot be read inside a timed run, so this one number comes from a file; everything else in the line is measured live."""
+    traffic, stamp = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes:"):
-                return float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            if line.startswith("kernel_source_sha256:"):
+                stamp = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
-
-
-def read_profile_avg_us(path, kernel_prefix):
-    """avg_us of the first kernel line starting with kernel_prefix in a committed rocprofv3 kernel-trace summary, or None."""
-    try:
-        for line in open(path):
-            if line.startswith(kernel_prefix):
-                return float(line[len(kernel_prefix):].split()[1])
-    except (OSError, ValueError, IndexError):
-        pass
-    return None
+        return None, None
+    return traffic, (stamp is None or stamp != source_sha(source_rel))
 
 
 def main():
@@ -63,6 +68,8 @@ def main():
     ap.add_argument("--weights", default="dense", choices=["dense", "int4"],
                     help="int4: 4-bit group weights with bf16 activations (W4A16, the paper's 13B setting); bf16 workloads only")
     ap.add_argument("--temperature", type=float, default=0.0, help="> 0: stochastic acceptance at that temperature instead of greedy")
+    ap.add_argument("--no-extras", action="store_true", help="default run only: skip the two short extra legs (long-context attention, "
+                    "1024-row projections) that reuse the stage's weights")
     ap.add_argument("--no-probes", action="store_true", help="skip the achievable-peak probes (pure streaming read, pure MFMA loop) and the "
                     "large-size KV compaction measurement")
     ap.add_argument("--batch", type=int, default=1, metavar="B",
@@ -113,6 +120,17 @@ def main():
         dfn, dlm, dls = up(fn), up(lm), None
         stage = fs.stage_from_config(cfg, dev_layers, dfn, dlm, max_seg=B * cfg.seg_len)
     torch.cuda.synchronize()
+    extras_on = (args.workload == "C2" and B == 1 and not w4 and not args.no_extras and not args.layers and not args.seg_len
+                 and args.temperature <= 0 and not args.no_head)
+    extra_stages = {}
+    if extras_on:
+        # the same device weights re-tiled into two more stages (same layer shape): the long-context workload (the one where
+        # tree attention carries weight) and the 1024-row chunk (the one where the projections are bound by the matrix units)
+        for name in ("C5", "P2"):
+            xc = synth.CONFIGS[name]
+            extra_stages[name] = fs.stage_from_config(xc, dev_layers, None, None, kv_capacity=xc.l_glo + xc.tree_size + xc.seg_len,
+                                                      max_tree=xc.tree_size, max_seg=xc.seg_len)
+        torch.cuda.synchronize()
     del dev_layers, dfn, dlm, dls
     torch.cuda.empty_cache()
     kv = stage.new_kv_cache()
@@ -284,12 +302,15 @@ def main():
         roofline = {"kernel": "wide_gemm_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up, %d rows)" % rows_per_launch, "bound": "mfma",
                     "achieved": round(gu_tf, 1), "peak": mfma_peak, "unit": "TFLOP/s", "frac": round(gu_tf / mfma_peak, 4),
                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_flops": gu_flops,
-                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower())) if B == 1 else None}
+                    "traffic": None}
+        if B == 1:
+            roofline["traffic"], roofline["traffic_stale"] = read_traffic(os.path.join(ROOT, "profiles", "gateup_%s_traffic.txt" % args.workload.lower()), GEMM_SRC)
     else:
         roofline = {"kernel": "skinny_gemm%s_kernel<EPI_SWIGLU> (RMSNorm + gate/up + SiLU*up)" % ("_w4" if w4 else ""), "bound": "hbm",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "avg_launch_us": round(gu_avg_ms * 1e3, 2), "algorithmic_bytes": gu_bytes,
-                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")))}
+                    "traffic": None}
+        roofline["traffic"], roofline["traffic_stale"] = read_traffic(os.path.join(ROOT, "profiles", "gateup_%s%s_traffic.txt" % (args.workload.lower(), "_w4" if w4 else "")), GEMM_SRC)
 
     # KV compaction of the step: rows kept in the cache that actually move (retained draft rows), read + written, K and V, all layers
     cp_ms, cp_n = prof["compact"]
@@ -309,6 +330,13 @@ def main():
                       "note": "one-pass reads of 176 MiB / 32 MiB per launch rotating through 3 GiB; register-resident 16x16x32 bf16 MFMA loop"}
         del big
         torch.cuda.empty_cache()
+        big = torch.empty((1 << 28) + 64, dtype=torch.uint8, device=dev)
+        achievable["fill_l2_hit_GBs_per_cu"] = round(fs.probe_fill(big, 256, 8, 64, 512, 1, True, 3) / 256, 1)
+        achievable["fill_beyond_l2_GBs_per_cu"] = round(fs.probe_fill(big, 256, 8, 512, 512, 1, True, 3) / 256, 1)
+        achievable["fill_note"] = ("rate at which one compute unit (all 256 at once) pulls data into LDS with direct-to-LDS loads: from its "
+                                   "XCD's L2 / from beyond it (128 MiB re-read cyclically); bounds the many-row projection kernels")
+        del big
+        torch.cuda.empty_cache()
         Tb = 1024
         # compaction only looks at the cache geometry, so a stage with the workload's layers / KV heads / head dim and
         # token-sized projections stands in (no second copy of the weights)
@@ -316,35 +344,84 @@ def main():
         lw_b = [{k: up(v) for k, v in synth.layer_weights(cfg_b, l, seed).items()} for l in range(cfg_b.n_layers)]
         stage_b = fs.stage_from_config(cfg_b, lw_b, kv_capacity=cfg.l_glo + Tb + 64, max_tree=Tb, max_seg=16)
         kv_b = stage_b.new_kv_cache()
-        keep = list(range(0, Tb, 2))
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 10
-        for _ in range(2):
-            stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
-        ev0.record()
-        for _ in range(reps):
-            stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
-        ev1.record()
-        torch.cuda.synchronize()
-        ms_b = ev0.elapsed_time(ev1) / reps
-        bytes_b = 2 * 2 * len(keep) * cfg.n_kv_heads * cfg.head_dim * elem * cfg.n_layers
-        kvc["kv_compact_large"] = {"rows_kept": len(keep), "of_tree_nodes": Tb, "algorithmic_bytes": bytes_b, "avg_us": round(ms_b * 1e3, 2),
-                                   "achieved_GBs": round(bytes_b / (ms_b * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
-                                   "frac": round(bytes_b / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # two retain sets of 512 of 1024 nodes: every other node (256-byte rows with 256-byte holes) and an accepted path of 4
+        # plus one contiguous run (what a subtree looks like when its nodes were appended together)
+        patterns = {"every_other_row": list(range(0, Tb, 2)), "path_plus_contiguous_run": [0, 1, 2, 3] + list(range(300, 808))}
+        for pname, keep in patterns.items():
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            for _ in range(2):
+                stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
+            ev0.record()
+            for _ in range(reps):
+                stage_b.kv_compact(kv_b, cfg.l_glo, cfg.l_glo + Tb, keep, n_acc=4)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms_b = ev0.elapsed_time(ev1) / reps
+            moved = sum(1 for j, i in enumerate(keep) if i != j)
+            bytes_b = 2 * 2 * moved * cfg.n_kv_heads * cfg.head_dim * elem * cfg.n_layers
+            entry = {"rows_kept": len(keep), "rows_moved": moved, "of_tree_nodes": Tb, "algorithmic_bytes": bytes_b, "avg_us": round(ms_b * 1e3, 2),
+                     "achieved_GBs": round(bytes_b / (ms_b * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "frac": round(bytes_b / (ms_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            if pname == "every_other_row":
+                kvc["kv_compact_large"] = entry
+            else:
+                kvc["kv_compact_large_" + pname] = entry
         del stage_b, kv_b, lw_b
 
-    # the same kernel's average duration in the committed rocprofv3 kernel trace (tool timestamps, without the two event
-    # records that bracket every launch of the live measurement and add about 2 us to it)
-    prof_us = None
-    if wide and args.workload == "P2" and B == 1:
-        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "wide_gemm_p2_kernel_trace.txt"), "void wide_gemm_kernel<2, false, 8, 4, 4, false>")
-    elif not wide and not w4 and args.workload == "C2" and B == 1:
-        prof_us = read_profile_avg_us(os.path.join(ROOT, "profiles", "bench_c2_kernel_trace.txt"), "void skinny_gemm_kernel<bool _Accum, int, E, 2, 2>")
-    if prof_us:
-        roofline["rocprof_avg_launch_us"] = prof_us
-        work = roofline.get("algorithmic_bytes", roofline.get("algorithmic_flops"))
-        scale = 1e9 if roofline["bound"] == "hbm" else 1e12
-        roofline["rocprof_frac"] = round(work / (prof_us * 1e-6) / scale / roofline["peak"], 4)
+    # the two extra legs of the default run: same weights, other geometry, a few steps each, every launch timed by events
+    extras = None
+    if extras_on:
+        extras = {}
+        for name, xst in extra_stages.items():
+            xc = synth.CONFIGS[name]
+            xkv = xst.new_kv_cache()
+            xkv[:, :, :, : xc.l_glo].normal_()   # timing only: any finite prefix will do
+            xtree = synth.config_tree(xc, seed)
+            xsegs = synth.segments(xtree.size, xc.seg_len)
+            xh = [torch.randn((n, xc.d_model), device=dev).to(tdt) for _, n in xsegs]
+            xo = [torch.empty_like(h) for h in xh]
+
+            def xstep():
+                for i, (off, n) in enumerate(xsegs):
+                    xst.tree_verify_stage(xkv, xc.l_glo, xc.l_glo + off, xh[i], off, xtree.parent[: off + n], xo[i])
+            xsteps = 5
+            for _ in range(2):
+                xstep()
+            torch.cuda.synchronize()
+            t0x = time.perf_counter()
+            for _ in range(xsteps):
+                xstep()
+            torch.cuda.synchronize()
+            x_ms = (time.perf_counter() - t0x) / xsteps * 1e3
+            xst.profile_begin(xsteps * len(xsegs) * (6 * xc.n_layers + 4) + 16)
+            for _ in range(xsteps):
+                xstep()
+            xp = xst.profile_end()
+            rows = min(xc.seg_len, xtree.size)
+            ent = {"workload": xc.name, "stage": "intermediate (no head)", "ms_per_step": round(x_ms, 4), "steps": xsteps,
+                   "rows_per_s": round(xtree.size / (x_ms * 1e-3), 1),
+                   "kernels": {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1]} for k, v in xp.items() if v[1]}}
+            if name == "C5":
+                xb = 2 * xc.n_kv_heads * xc.head_dim * elem * sum(xc.l_glo + o + n for o, n in xsegs) / len(xsegs)
+                at = xp["attn"][0] / xp["attn"][1]
+                ent["tree_attention"] = {"kernel": "tree_attn_kernel + attn_merge_kernel", "bound": "hbm", "algorithmic_bytes": int(xb),
+                                         "avg_us": round(at * 1e3, 2), "achieved": round(xb / (at * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                                         "unit": "GB/s", "frac": round(xb / (at * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            else:
+                gu = xp["gateup"][0] / xp["gateup"][1]
+                fl = 2.0 * rows * 2 * xc.d_ffn * xc.d_model
+                allf = 2.0 * rows * (2 * xc.n_q_heads * xc.head_dim * xc.d_model + 2 * xc.n_kv_heads * xc.head_dim * xc.d_model + 3 * xc.d_ffn * xc.d_model)
+                allms = sum(xp[k][0] / xp[k][1] for k in ("qkv", "oproj", "gateup", "down"))
+                ent["gateup_mfma"] = {"kernel": "gate/up projection, %d rows" % rows, "bound": "mfma", "algorithmic_flops": fl, "avg_us": round(gu * 1e3, 2),
+                                      "achieved": round(fl / (gu * 1e-3) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                      "frac": round(fl / (gu * 1e-3) / 1e12 / 2500.0, 4)}
+                ent["projections_mfma_frac"] = round(allf / (allms * 1e-3) / 1e12 / 2500.0, 4)
+            extras[name] = ent
+            del xkv, xh, xo
+            xst.close()
+        extra_stages.clear()
+        torch.cuda.empty_cache()
 
     result = {
         "metric": "verified draft tokens/sec per stage; MFMA util (GEMMs) + HBM GB/s (tree attn)",
@@ -371,6 +448,7 @@ def main():
                       "note": ("rows per launch = segment length: MFMA-bound projection kernel" if wide else
                                "rows per launch = segment length: the projections are weight-stream bound, see roofline")},
         "kernels": kern,
+        "extra_legs": extras,
         "accept": {"n_acc": out_res.n_acc, "continuous": out_res.continuous, "n_retain": out_res.n_retain},
         "setup_s": round(setup_s, 1),
     }

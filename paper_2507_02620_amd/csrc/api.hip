@@ -245,12 +245,13 @@ struct Profiler {
 
 // Tuning knobs from the environment, read once when the stage is created (a launch never calls getenv).
 struct Tunables {
-    int attn_wgs, attn_mtw, wide_rows, mid_rows, block_gemm;
+    int attn_wgs, attn_mtw, wide_rows, mid_rows, block_gemm, compact_cb;
     void read() {
         attn_wgs = env_int("FLOWSPEC_ATTN_WGS", 0);    // > 0: workgroups the attention split plan aims for
         attn_mtw = env_int("FLOWSPEC_ATTN_MTW", 0);    // > 0: row tiles per wave of the attention kernel
         wide_rows = env_int("FLOWSPEC_WIDE_ROWS", 65); // stacked rows from which every projection takes the many-row kernel
         mid_rows = env_int("FLOWSPEC_MID_ROWS", 17);   // ... from which the wide projections do
+        compact_cb = env_int("FLOWSPEC_COMPACT_CB", 0);  // KV compaction: column blocks per row (0: by the grid size)
         block_gemm = env_int("FLOWSPEC_BLOCK_GEMM", -1);  // 256-row projection kernel: 0 never, 1 whenever possible, else by rule
     }
 };
@@ -790,11 +791,12 @@ int fs_kv_compact(fs_stage* st, fs_kv_cache kv, int l_glo, int l_cache, const in
     a.base = kv.base; a.stride_layer = kv.stride_layer; a.stride_kv = kv.stride_kv; a.stride_head = kv.stride_head; a.stride_tok = kv.stride_tok;
     a.elem_bytes = st->elem; a.n_layers = d.n_layers; a.n_kv_heads = d.n_kv_heads; a.hd = d.head_dim;
     a.l_glo = l_glo; a.l_cache = l_cache; a.new_len = new_len;
-    // split rows over column blocks until the grid has a few workgroups per compute unit
+    // split rows over column blocks until the grid has about four workgroups per compute unit (measured at 512 moved rows per
+    // head, 32 heads x 8 layers: 512 workgroups 21.8 us, 1024 20.8 us, 2048 28 us)
     const int ppr = d.head_dim * st->elem / 16;
     int cb = 1;
-    // (more, smaller workgroups were measured slower: 1024 -> 0.97x, 2048 -> 0.75x, 4096 -> 0.56x at 512 moved rows)
-    while ((long long)d.n_layers * 2 * d.n_kv_heads * cb < 512 && cb * 2 <= ppr) cb *= 2;
+    while ((long long)d.n_layers * 2 * d.n_kv_heads * cb < 1024 && cb * 2 <= ppr) cb *= 2;
+    if (st->tun.compact_cb > 0 && st->tun.compact_cb <= ppr && ppr % st->tun.compact_cb == 0) cb = st->tun.compact_cb;
     a.colblocks = cb;
     HIP_TRY_K(st, FS_K_COMPACT, (hipStream_t)stream, launch_kv_compact(a, host, (hipStream_t)stream));
     return FS_OK;

@@ -394,10 +394,12 @@ hipError_t launch_accept(const int32_t* amax, const int32_t* token, const int32_
 // towards lower slots (I_incache[j] >= j), in place.  A block moves CH rows per step: all loads of the step,
 // a barrier, then all stores.  Stores of a step only hit slots below every source of later steps, and
 // different blocks touch disjoint bytes, so no other ordering is needed.
-#define CMP_THREADS 256
-#define CMP_UNROLL 4
-
-__global__ void __launch_bounds__(CMP_THREADS) kv_compact_kernel(const CompactArgs a, const IdxList host) {
+// 256 threads with 8 pieces of 16 bytes in flight each (measured at 512 moved rows per head, 134 MB read + written: 4 pieces
+// 21.8 us, 8 pieces 20.8 us, 16 pieces or 512 / 1024 threads 36 - 60 us: a launch whose workgroups all read and then all
+// write floods the L2 with dirty lines; streaming stores 21.5 us, streaming loads 28.5 us).  The pieces are native 4 x 32-bit
+// vectors: with the runtime's uint4 struct type the same loop took 32 - 36 us.
+template <int THREADS, int UNROLL>
+__global__ void __launch_bounds__(THREADS) kv_compact_kernel(const CompactArgs a, const IdxList host) {
     __shared__ short src[1024];
     __shared__ int sh_n;
     const int tid = threadIdx.x;
@@ -409,7 +411,7 @@ __global__ void __launch_bounds__(CMP_THREADS) kv_compact_kernel(const CompactAr
     __syncthreads();
     // I_incache is a prefix of the ascending retain list
     int cntl = 0;
-    for (int j = tid; j < n_retain && j < 1024; j += CMP_THREADS) {
+    for (int j = tid; j < n_retain && j < 1024; j += THREADS) {
         const int i = a.retain_dev ? a.retain_dev[j] : (int)host.v[j];
         src[j] = (short)i;
         cntl += (i < n_draft);
@@ -428,30 +430,35 @@ __global__ void __launch_bounds__(CMP_THREADS) kv_compact_kernel(const CompactAr
     const size_t tok_bytes = (size_t)a.stride_tok * a.elem_bytes;
     const int ppr = a.hd * a.elem_bytes / 16;      // 16-byte pieces per row
     const int ppb = ppr / a.colblocks;             // pieces per row handled by this block
-    const int rows_per_pass = CMP_THREADS / ppb;   // ppb divides CMP_THREADS (checked on the host)
+    const int rows_per_pass = THREADS / ppb;       // ppb divides THREADS (checked on the host)
     const int piece = cb * ppb + tid % ppb, rloc = tid / ppb;
-    const int CH = rows_per_pass * CMP_UNROLL;
+    const int CH = rows_per_pass * UNROLL;
     // leading rows that already sit in place need no move
     int j0 = 0;
     while (j0 < n_in && src[j0] == j0) ++j0;
     for (int jb = j0; jb < n_in; jb += CH) {
-        uint4 buf[CMP_UNROLL];
+        u32x4 buf[UNROLL];
+        // no branch around a load: rows past the end re-read the last one (never stored), so the loads of a step go out
+        // back to back and the compiler counts them exactly instead of waiting for each in turn
 #pragma unroll
-        for (int u = 0; u < CMP_UNROLL; ++u) {
-            const int j = jb + u * rows_per_pass + rloc;
-            if (j < n_in) buf[u] = *(const uint4*)(hp + (size_t)(a.l_glo + src[j]) * tok_bytes + (size_t)piece * 16);
+        for (int u = 0; u < UNROLL; ++u) {
+            const int j = min(jb + u * rows_per_pass + rloc, n_in - 1);
+            const u32x4* sp = (const u32x4*)(hp + (size_t)(a.l_glo + src[j]) * tok_bytes + (size_t)piece * 16);
+            buf[u] = *sp;
         }
         __syncthreads();
 #pragma unroll
-        for (int u = 0; u < CMP_UNROLL; ++u) {
+        for (int u = 0; u < UNROLL; ++u) {
             const int j = jb + u * rows_per_pass + rloc;
-            if (j < n_in) *(uint4*)(hp + (size_t)(a.l_glo + j) * tok_bytes + (size_t)piece * 16) = buf[u];
+            u32x4* dp = (u32x4*)(hp + (size_t)(a.l_glo + j) * tok_bytes + (size_t)piece * 16);
+            if (j < n_in) *dp = buf[u];
         }
+        __syncthreads();  // (only matters with several steps) the step's stores are issued before the next step's loads
     }
 }
 
 hipError_t launch_kv_compact(const CompactArgs& a, const IdxList& host, hipStream_t s) {
-    hipLaunchKernelGGL(kv_compact_kernel, dim3(a.n_layers * 2 * a.n_kv_heads, a.colblocks), dim3(CMP_THREADS), 0, s, a, host);
+    hipLaunchKernelGGL((kv_compact_kernel<256, 8>), dim3(a.n_layers * 2 * a.n_kv_heads, a.colblocks), dim3(256), 0, s, a, host);
     return hipGetLastError();
 }
 
