@@ -446,7 +446,19 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
     const int nw = a.nwc <= 4 ? 4 : 8;  // every wave stages the tiles; the first a.nwc also compute
     dim3 grid(a.n_splits, a.Hkv, row_blocks * a.n_req), block(nw * 64);
     const bool deep = MTW == 1 && a.tiles_per_split >= 4;  // two tiles in flight pay from about 4 tiles per workgroup on
-    if (MTW == 1 && nw == 4 && deep)
+    // three or four tiles in flight: 16-bit types only (the 32-bit kernels would spill), splits of at least two rounds of the ring
+    bool done = false;
+    if constexpr (sizeof(T) == 2) {
+        if (MTW == 1 && nw == 4 && deep && a.nset >= 4 && a.tiles_per_split >= 8) {
+            hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 4, true>), grid, block, 0, s, row_blocks, a);
+            done = true;
+        } else if (MTW == 1 && nw == 4 && deep && a.nset == 3 && a.tiles_per_split >= 6) {
+            hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 3, true>), grid, block, 0, s, row_blocks, a);
+            done = true;
+        }
+    }
+    if (done) {
+    } else if (MTW == 1 && nw == 4 && deep)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 2, true>), grid, block, 0, s, row_blocks, a);
     else if (MTW == 1 && nw == 4)
         hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 1, true>), grid, block, 0, s, row_blocks, a);
@@ -476,25 +488,40 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
     return e;
 }
 
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int* NWC, int* MTW,
-               int* row_blocks, int* n_splits, int* tiles_per_split) {
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
+               int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset) {
     const int R = G * M, mtiles = (R + 15) / 16;
+    const int BS = attn_tile_slots(elem_bytes, hd);
+    const int ntiles = (L + BS - 1) / BS;
     // up to 8 compute waves per workgroup; with 4 to 16 row tiles every wave takes 2 of them (each K/V fragment read from
-    // LDS then serves 32 rows; 64 rows at a 16k context: 64.5 -> 62.8 us).  Beyond that there are row blocks enough to fill
-    // the chip with few or no KV splits, and one tile per wave is faster (1024-row chunk: 74 -> 65 us, no merge pass).
+    // LDS then serves 32 rows).  Beyond that there are row blocks enough to fill the chip with few or no KV splits, and one
+    // tile per wave is faster (1024-row chunk: 74 -> 65 us, no merge pass).
     int mtw = (mtiles >= 4 && mtiles <= 16) ? 2 : 1;
+    // about 2 workgroups per CU for long contexts, fewer and longer splits for short ones (latency-bound: C2 256)
+    int target = ntiles <= 32 ? 256 : 512;
+    int ring = 2;
+    // Long context, at most 64 rows per KV head (4 row tiles, one per wave) and 16-bit K/V: one workgroup per compute unit with
+    // three K/V tiles in flight does better than two workgroups with one or two tiles each, and halves the partial results
+    // the merge has to read (16k context, 64 rows: 59.0 -> 54.0 us; four tiles in flight 69 us, 320 workgroups 72 us).
+    const bool deep_ring = elem_bytes == 2 && mtiles <= 4 && ntiles >= 6 * ((256 + Hkv - 1) / Hkv);
+    if (deep_ring) {
+        mtw = 1;
+        target = 256;
+        ring = 3;
+    }
     if (mtw_override > 0) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
+    if (wgs_override > 0) target = wgs_override;
+    if (nset_override > 0) ring = nset_override;
     int nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
     *NWC = nw;
     *MTW = mtw;
+    *nset = ring;
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);
-    const int BS = attn_tile_slots(elem_bytes, hd);
-    const int ntiles = (L + BS - 1) / BS;
-    // about 2 workgroups per CU for long contexts (C5: 512 best, 384 and 768 +12 %); short ones are latency-bound and
-    // do slightly better with fewer, longer splits (C2: 256)
-    const int target = wgs_override > 0 ? wgs_override : (ntiles <= 32 ? 256 : 512);
-    int want = (target + Hkv * *row_blocks - 1) / (Hkv * *row_blocks);
+    const int per_split = Hkv * *row_blocks;  // workgroups per KV split
+    int want = (target + per_split - 1) / per_split;
+    // one workgroup per compute unit: a handful of workgroups beyond 256 would make a second round of their own
+    if (deep_ring && wgs_override <= 0 && want * per_split > 256 && want > 1) --want;
     if (want > max_splits) want = max_splits;
     if (want > ntiles) want = ntiles;
     if (want < 1) want = 1;

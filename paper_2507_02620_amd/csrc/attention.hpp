@@ -25,13 +25,15 @@ struct AttnArgs {
     float* part_o;        // [n_splits][Hkv][Rpad][hd], Rpad >= G * rows; row G * row0 + rho of a request
     float* part_ml;       // [n_splits][Hkv][Rpad][2]
     int nwc;              // compute waves per workgroup (workgroups have at least 4 waves for staging)
+    int nset;             // tiles in flight per workgroup for long splits with one row tile per wave (2 .. 4; set by attn_plan)
     AttnReq req[ATTN_MAX_REQ];  // last: the fields above stay within the first cache lines of the kernel-argument segment
 };
 
 // slots per LDS tile for a given element size and head dim
 static inline int attn_tile_slots(int elem_bytes, int hd) { return elem_bytes * hd >= 512 ? 32 : 64; }
 
-// wgs_override / mtw_override > 0 replace the plan's own choice of the workgroup target and of the row tiles per wave (tuning knobs)
-void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int* NWC, int* MTW,
-               int* row_blocks, int* n_splits, int* tiles_per_split);
+// wgs_override / mtw_override / nset_override > 0 replace the plan's own choice of the workgroup target, of the row tiles per wave and of
+// the K/V tiles in flight per workgroup (tuning knobs)
+void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
+               int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset);
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s);

@@ -86,6 +86,23 @@ def test_long_kv_splits(name, cfg, seg, wgs, monkeypatch):
     _check_stage(cfg.with_(name=name, seg_len=seg), 5, seg)
 
 
+@pytest.mark.parametrize("name,cfg,seg,wgs,nset", [
+    # three and four K/V tiles in flight per workgroup: 13 tiles in one split (ring rounds + a ragged tail), two splits of 7 / 6,
+    # head dim 64, and a context so short that most tiles are draft slots (mask words fetched ahead of every tile)
+    ("ring3-13-tiles", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 4, 3),
+    ("ring4-13-tiles", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 4, 4),
+    ("ring3-two-splits", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 8, 3),
+    ("ring4-hd64-17-tiles", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=8, head_dim=64, l_glo=1040, tree_size=40), 16, 8, 4),
+    ("ring4-mostly-draft-slots", SMALL_BF16.with_(l_glo=8, tree_size=640, max_depth=14), 16, 4, 4),
+    ("ring3-mostly-draft-slots", SMALL_BF16.with_(l_glo=70, tree_size=500, max_depth=14), 16, 4, 3),
+])
+def test_long_kv_splits_deeper_rings(name, cfg, seg, wgs, nset, monkeypatch):
+    monkeypatch.setenv("FLOWSPEC_ATTN_WGS", str(wgs))
+    monkeypatch.setenv("FLOWSPEC_ATTN_NSET", str(nset))
+    monkeypatch.setenv("FLOWSPEC_ATTN_MTW", "1")
+    _check_stage(cfg.with_(name=name, seg_len=seg), 5, seg)
+
+
 @pytest.mark.parametrize("name,cfg,seg,wgs", [
     # one case per tree-attention variant, each with a context so short (l_glo <= 16) that the draft slots — the part the
     # ancestor mask governs — carry most of the attention weight
