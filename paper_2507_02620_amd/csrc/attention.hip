@@ -445,14 +445,17 @@ template <typename T, int HD>
 static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
     const int nw = a.nwc <= 4 ? 4 : 8;  // every wave stages the tiles; the first a.nwc also compute
     dim3 grid(a.n_splits, a.Hkv, row_blocks * a.n_req), block(nw * 64);
-    const bool deep = MTW == 1 && a.tiles_per_split >= 4;  // two tiles in flight pay from about 4 tiles per workgroup on
-    // three or four tiles in flight: 16-bit types only (the 32-bit kernels would spill), splits of at least two rounds of the ring
+    // K/V tiles in flight per workgroup (a.nset, chosen by attn_plan): rings of 3 and 4 exist for 16-bit types with 4 waves only
+    // (the 32-bit kernels would spill), rings of 2 only with one row tile per wave
+    int ring = MTW == 1 ? a.nset : 1;
+    if (ring > 2 && (sizeof(T) != 2 || nw != 4)) ring = 2;
+    const bool deep = ring >= 2;
     bool done = false;
     if constexpr (sizeof(T) == 2) {
-        if (MTW == 1 && nw == 4 && deep && a.nset >= 4 && a.tiles_per_split >= 8) {
+        if (MTW == 1 && nw == 4 && ring >= 4) {
             hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 4, true>), grid, block, 0, s, row_blocks, a);
             done = true;
-        } else if (MTW == 1 && nw == 4 && deep && a.nset == 3 && a.tiles_per_split >= 6) {
+        } else if (MTW == 1 && nw == 4 && ring == 3) {
             hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 3, true>), grid, block, 0, s, row_blocks, a);
             done = true;
         }
@@ -511,12 +514,10 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     }
     if (mtw_override > 0) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
     if (wgs_override > 0) target = wgs_override;
-    if (nset_override > 0) ring = nset_override;
     int nw = (mtiles + mtw - 1) / mtw;
     if (nw > 8) nw = 8;
     *NWC = nw;
     *MTW = mtw;
-    *nset = ring;
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);
     const int per_split = Hkv * *row_blocks;  // workgroups per KV split
     int want = (target + per_split - 1) / per_split;
@@ -527,6 +528,14 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     if (want < 1) want = 1;
     *tiles_per_split = (ntiles + want - 1) / want;
     *n_splits = (ntiles + *tiles_per_split - 1) / *tiles_per_split;
+    // tiles in flight: two pay from about 4 tiles per workgroup on, three need two rounds of the ring; never more than the split has
+    if (nset_override > 0)
+        ring = nset_override;
+    else if (ring == 3 && *tiles_per_split < 6)
+        ring = 2;
+    if (nset_override <= 0 && *tiles_per_split < 4) ring = 1;
+    if (ring > *tiles_per_split) ring = *tiles_per_split;
+    *nset = ring < 1 ? 1 : ring;
 }
 
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {
