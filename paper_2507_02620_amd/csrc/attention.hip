@@ -492,7 +492,7 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
 }
 
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
-               int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset) {
+               int nwc_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset) {
     const int R = G * M, mtiles = (R + 15) / 16;
     const int BS = attn_tile_slots(elem_bytes, hd);
     const int ntiles = (L + BS - 1) / BS;
@@ -512,10 +512,20 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
         target = 256;
         ring = 3;
     }
+    // Long context, 9 to 16 row tiles on few KV heads (grouped-query attention with a wide group): one 8-wave workgroup per
+    // head and split leaves half the chip idle and needs many splits, each writing partial results for every row.  Four
+    // one-tile waves per workgroup give row blocks instead, which re-read K/V from L2 (4k context, 4 KV heads x 224 rows:
+    // 23.2 -> 18.8 us with the merge; 2, 5 or 7 waves, or two tiles per wave, are all slower).
+    int nw_cap = 8;
+    if (!deep_ring && mtiles > 8 && mtiles <= 16 && Hkv <= 8 && ntiles > 32) {
+        mtw = 1;
+        nw_cap = 4;
+    }
     if (mtw_override > 0) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
     if (wgs_override > 0) target = wgs_override;
+    if (nwc_override > 0) nw_cap = nwc_override < 8 ? nwc_override : 8;
     int nw = (mtiles + mtw - 1) / mtw;
-    if (nw > 8) nw = 8;
+    if (nw > nw_cap) nw = nw_cap;
     *NWC = nw;
     *MTW = mtw;
     *row_blocks = (mtiles + nw * mtw - 1) / (nw * mtw);

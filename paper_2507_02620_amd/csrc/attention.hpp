@@ -35,5 +35,5 @@ static inline int attn_tile_slots(int elem_bytes, int hd) { return elem_bytes * 
 // wgs_override / mtw_override / nset_override > 0 replace the plan's own choice of the workgroup target, of the row tiles per wave and of
 // the K/V tiles in flight per workgroup (tuning knobs)
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
-               int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset);
+               int nwc_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset);
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s);

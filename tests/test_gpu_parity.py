@@ -64,6 +64,9 @@ SMALL_BF16 = synth.StageConfig("small-bf16", "bf16", 2, 512, 4, 4, 128, 1376, 20
     ("hd64", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=8, head_dim=64), 16),
     ("seg64", SMALL_BF16.with_(tree_size=130, l_glo=1000, max_depth=12), 64),
     ("f32-hd128", SMALL_BF16.with_(dtype="f32", l_glo=100), 16),
+    # one KV head under a group of 8 query heads, 27-row segments (14 row tiles, the last one ragged) and 34 K/V tiles: the
+    # split plan's four-wave row blocks for wide groups on a long context
+    ("gqa-wide-group-long-context", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=1, d_model=1024, l_glo=2100, tree_size=60), 27),
 ])
 def test_small_stages(name, cfg, seg):
     _check_stage(cfg.with_(name=name, seg_len=seg), 2, seg)
@@ -113,6 +116,7 @@ def test_long_kv_splits_deeper_rings(name, cfg, seg, wgs, nset, monkeypatch):
     ("mask-hd64", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=8, head_dim=64, l_glo=5, tree_size=200, max_depth=10), 16, 8),
     ("mask-gqa", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=12, tree_size=100, max_depth=10), 32, None),
     ("mask-gqa-row-blocks", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=3, tree_size=200, max_depth=10), 80, None),
+    ("mask-gqa-four-wave-row-blocks", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=12, tree_size=200, max_depth=10), 48, -4),
 ])
 def test_bf16_comparison_would_notice_a_wrong_mask(name, cfg, seg, wgs, monkeypatch):
     """The bf16 tolerance is wide, so these cases show that the comparison still discriminates: the HIP path's distance
@@ -120,7 +124,10 @@ def test_bf16_comparison_would_notice_a_wrong_mask(name, cfg, seg, wgs, monkeypa
     depths (same positions) but other ancestors."""
     from tests.gpu_util import max_rel_err
     from tests.helpers import make_oracle_stage, reparent_same_depth, verify_whole_tree
-    if wgs:
+    if wgs and wgs < 0:  # at most -wgs one-tile waves per workgroup: row blocks of four-wave workgroups
+        monkeypatch.setenv("FLOWSPEC_ATTN_NWC", str(-wgs))
+        monkeypatch.setenv("FLOWSPEC_ATTN_MTW", "1")
+    elif wgs:
         monkeypatch.setenv("FLOWSPEC_ATTN_WGS", str(wgs))
     cfg = cfg.with_(name=name, seg_len=seg)
     p, tree, o_out, g_out = _check_stage(cfg, 7, seg)
