@@ -48,6 +48,9 @@ def _run_batch(cfg, specs, seed, head=False, w4=False):
      [(50, 40, 6, 3, 16, 16), (0, 20, 4, 2, 0, 9), (130, 64, 8, 0, 32, 16), (77, 33, 5, 3, 16, 17)]),
     ("many-rows", synth.StageConfig("b-wide", "bf16", 2, 512, 4, 4, 128, 1408, 0, 0, 64, 16, 6, 3),
      [(100 + 13 * i, 48, 6, 3, 16, 16) for i in range(10)]),           # 160 stacked rows: the MFMA-bound projection kernel
+    # one KV head under 8 query heads, long contexts: row blocks of four one-tile waves; the shorter request has no third row block
+    ("wide-group-long-context", synth.StageConfig("b-gqa", "bf16", 1, 1024, 8, 1, 128, 1408, 0, 0, 64, 16, 6, 3),
+     [(2100, 40, 6, 3, 16, 20), (1500, 30, 5, 3, 16, 12)]),
     ("f32", synth.StageConfig("b-f32", "f32", 1, 256, 4, 4, 64, 688, 0, 0, 64, 16, 5, 3),
      [(30, 24, 5, 3, 8, 8), (64, 16, 4, 2, 0, 16), (5, 40, 6, 3, 24, 16)]),
 ])
