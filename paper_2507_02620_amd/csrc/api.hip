@@ -67,6 +67,8 @@ int choose_nt(int tiles, bool pair, int max_seg, const char* env, bool wide_n = 
     // segments of more than 32 rows: QKV and the LM head do better with 4 tiles per group (measured at 64 rows: QKV 42 -> 34 us,
     // head 92 -> 67 us; gate/up and the d_model-wide projections do not)
     if (max_seg > 32 && wide_n && tiles / 4 >= 160) nt = 4;
+    // two row tiles (17 to 32 rows): the same from 192 groups on (24 rows, 960 tiles: QKV 33.6 -> 30.3 us, 2000 tiles: head 55.9 -> 54.0 us)
+    if (max_seg > 16 && wide_n && tiles / 4 >= 192) nt = 4;
     int o = env_int(env, 0);
     if (o == 1 || o == 2 || o == 4) nt = (pair && o == 1) ? 2 : o;
     return nt;
@@ -82,7 +84,8 @@ void plan_gemm(GemmPlan& g, int tiles, int K, int elem, bool pair, int max_seg, 
         // a 4-bit tile is a quarter of the bytes: larger groups keep the per-workgroup stream long enough;
         // 64-row segments stay at NT <= 2 (registers)
         int nt = pair ? 2 : 1;
-        if (tiles / 4 >= 256 && max_seg <= 32) nt = 4;
+        // (QKV and the LM head already from 192 groups on: 24 rows, 960 tiles: QKV 27.4 -> 22.2 us; 16 rows, 768 tiles: 14.5 -> 13.8 us)
+        if ((tiles / 4 >= 256 || (wide_n && tiles / 4 >= 192)) && max_seg <= 32) nt = 4;
         else if (tiles / 2 >= 128) nt = 2;
         const int o = env_int(env_nt, 0);
         if (o == 1 || o == 2 || o == 4) nt = (pair && o == 1) ? 2 : o;
