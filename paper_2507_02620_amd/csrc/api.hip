@@ -248,11 +248,12 @@ struct Profiler {
 
 // Tuning knobs from the environment, read once when the stage is created (a launch never calls getenv).
 struct Tunables {
-    int attn_wgs, attn_mtw, attn_nset, attn_nwc, wide_rows, mid_rows, block_gemm, compact_cb;
+    int attn_wgs, attn_mtw, attn_nset, attn_nwc, attn_dma, wide_rows, mid_rows, block_gemm, compact_cb;
     void read() {
         attn_wgs = env_int("FLOWSPEC_ATTN_WGS", 0);    // > 0: workgroups the attention split plan aims for
         attn_mtw = env_int("FLOWSPEC_ATTN_MTW", 0);    // > 0: row tiles per wave of the attention kernel
         attn_nwc = env_int("FLOWSPEC_ATTN_NWC", 0);    // > 0: at most this many row-tile waves per workgroup (more row blocks)
+        attn_dma = env_int("FLOWSPEC_ATTN_DMA", 0);    // 1: never the direct-to-LDS attention kernel; 2 .. 4: always, with so many tile buffers
         attn_nset = env_int("FLOWSPEC_ATTN_NSET", 0);  // > 0: K/V tiles in flight per workgroup on long splits
         wide_rows = env_int("FLOWSPEC_WIDE_ROWS", 65); // stacked rows from which every projection takes the many-row kernel
         mid_rows = env_int("FLOWSPEC_MID_ROWS", 17);   // ... from which the wide projections do
@@ -583,8 +584,8 @@ static int verify_batch(fs_stage* st, const fs_batch_item* items, int n, const v
         ++rq;
     }
     int aMTW, aRB;
-    attn_plan(st->elem, hd, max_M, G, d.n_kv_heads * n_live, max_L, kMaxSplits, st->tun.attn_wgs, st->tun.attn_mtw, st->tun.attn_nset, st->tun.attn_nwc, &at.nwc, &aMTW, &aRB, &at.n_splits,
-              &at.tiles_per_split, &at.nset);
+    attn_plan(st->elem, hd, max_M, G, d.n_kv_heads * n_live, max_L, kMaxSplits, st->tun.attn_wgs, st->tun.attn_mtw, st->tun.attn_nset, st->tun.attn_nwc,
+              st->tun.attn_dma, &at.nwc, &aMTW, &aRB, &at.n_splits, &at.tiles_per_split, &at.nset, &at.dma);
 
     // 4-bit stages: activations entering a normed projection carry the norm's gain, and the rows' sums of squares
     // travel beside them as partial sums (see GemmArgs::gain_next)

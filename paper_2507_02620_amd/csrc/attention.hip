@@ -18,6 +18,8 @@
 // attn_merge_kernel combines them in a fixed order (deterministic).  (Letting the last workgroup to arrive do
 // the merge was measured and rejected: the device-scope fences it needs write back and invalidate the whole
 // per-XCD L2 once per workgroup, several times the cost of a second launch.)
+// (tree_attn_dma_kernel below is the variant for 16-bit K/V of head dim 128 with at most four row tiles: its tiles go from
+// global memory straight into LDS.)
 // All threads of the workgroup (256 or 512) stage a tile together; the next tile's global loads — the next two for long
 // splits — are issued before the current tile is computed, so HBM latency overlaps the MFMA work.  The kernel is bound
 // by that stream: with the arithmetic removed it is only about 7 % faster at a 16k context.
@@ -431,6 +433,273 @@ __global__ void __launch_bounds__(NWAVES * 64) __attribute__((amdgpu_waves_per_e
 }
 
 
+// ---- variant whose K/V tiles go straight from global memory into LDS ------------------------------------------------
+// bf16, head dim 128, one row tile per wave, 4 waves.  The tile fetch is the direct-to-LDS load: no registers hold a tile in
+// flight, so NBUF - 1 whole tiles (32 KiB each) are in flight per workgroup, behind ONE barrier per tile:
+//     wait (own loads of tile t landed, own LDS reads of tile t - 1 done) -> barrier -> issue tile t + NBUF - 1 into the
+//     buffer tile t - 1 used -> compute tile t.
+// Such a load writes 64 lanes x 16 bytes contiguously, so rows cannot be padded; instead the 16-byte chunk c of slot row r
+// sits at chunk position c ^ (r & 15) (each lane chooses which global chunk it fetches), which spreads the fragment reads
+// of 16 rows over all banks as the padding does.  The barrier is the bare instruction with explicit wait counts: the fence
+// of __syncthreads would wait for every tile in flight.  One array per buffer: distinct objects, so that the compiler's
+// own tracking of the direct-to-LDS loads never ties a read of one buffer to a load into another.
+
+template <int NBUF, bool STREAM>
+__global__ void __launch_bounds__(256) tree_attn_dma_kernel(int row_blocks, const AttnArgs a) {
+    using T = bf16_t;
+    using E = Elem<T>;
+    using frag_t = E::frag_t;
+    constexpr int HD = 128, BS = 64, KT = E::KT, EPF = E::EPF;
+    constexpr int NKT = HD / KT, NHT = HD / 16, NSUB = EPF / 4, NPF = BS / (16 * NSUB);
+    constexpr int ROWB = HD * (int)sizeof(T);   // 256 bytes per K or V row in LDS
+    constexpr int KBYTES = BS * ROWB;           // K part of a buffer; V follows
+    constexpr int LPT = 8;                      // direct-to-LDS loads per wave and tile (4 K + 4 V, 4 rows each)
+    constexpr int AUX = STREAM ? 2 : 0;         // non-temporal when one row block reads the K/V once
+    static_assert(NBUF >= 2 && NBUF <= 4 && LPT * (NBUF - 1) < 64, "vmcnt is a 6-bit counter");
+    __shared__ __align__(1024) unsigned char tb0[2 * KBYTES];
+    __shared__ __align__(1024) unsigned char tb1[2 * KBYTES];
+    __shared__ __align__(1024) unsigned char tb2[NBUF >= 3 ? 2 * KBYTES : 16];
+    __shared__ __align__(1024) unsigned char tb3[NBUF >= 4 ? 2 * KBYTES : 16];
+    auto buf_at = [&](int j) -> unsigned char* { return j == 0 ? tb0 : (j == 1 ? tb1 : (j == 2 ? tb2 : tb3)); };
+
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = lane & 15, g = lane >> 4;
+    const int split = blockIdx.x, kvh = blockIdx.y, rqi = blockIdx.z / row_blocks, rb = blockIdx.z % row_blocks;
+    const AttnReq rq = a.req[rqi];
+    const int M = rq.M, L = rq.L, l_glo = rq.l_glo, row0 = rq.row0;
+    const int R = a.G * M;
+    const bool dead = rb * a.nwc * 16 >= R;  // a shorter request of the batch may have no such row block
+    const int ntiles = dead ? 0 : (L + BS - 1) / BS;
+    const int t0 = split * a.tiles_per_split, t1 = min(ntiles, t0 + a.tiles_per_split);
+    const bool computes = (w < a.nwc) && ((rb * a.nwc + w) * 16 < R);
+
+    const int rho = (rb * a.nwc + w) * 16 + r16;
+    const bool rok = computes && rho < R;
+    const int rr = rok ? rho : 0;
+    const int seg_r = row0 + rr % M;
+    frag_t qf[NKT];
+    {
+        const int qh = kvh * a.G + rr / M;
+        const T* qp = (const T*)a.q + (size_t)seg_r * (a.Hq * HD) + (size_t)qh * HD + g * EPF;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) qf[kt] = rok ? *(const frag_t*)(qp + kt * KT) : E::zero();
+    }
+    f32x4 acc[NHT];
+#pragma unroll
+    for (int nt = 0; nt < NHT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = NEG_BIG, lrun = 0.f;
+
+    const unsigned char* kbase = (const unsigned char*)((const T*)rq.kbase + a.layer_off + (size_t)kvh * a.stride_head);
+    const unsigned char* vbase = kbase + (size_t)a.stride_kv * sizeof(T);
+    // Load i of this wave brings slot rows 16 w + 4 i .. + 3 of the tile: the lane's row and (swizzled) chunk of it.  Slots beyond
+    // L - 1 re-read the last valid row (they are masked below).
+    const unsigned row_bytes = (unsigned)(a.stride_tok * sizeof(T));
+    const unsigned last_row = (unsigned)(L - 1) * row_bytes;
+    unsigned row_off[4], col_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 4 * i + (lane >> 4);  // row & 15
+        row_off[i] = (unsigned)(16 * w + r) * row_bytes;
+        col_off[i] = (unsigned)(((lane & 15) ^ r) * 16);
+    }
+    auto issue = [&](int tile, unsigned char* buf) {
+        const unsigned t = (unsigned)(tile * BS) * row_bytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned off = min(row_off[i] + t, last_row) + col_off[i];
+            unsigned char* dst = buf + (16 * w + 4 * i) * ROWB;  // wave-uniform; the load adds lane * 16
+            __builtin_amdgcn_global_load_lds(FS_GLB_PTR(kbase + off), FS_LDS_PTR(dst), 16, 0, AUX);
+            __builtin_amdgcn_global_load_lds(FS_GLB_PTR(vbase + off), FS_LDS_PTR(dst + KBYTES), 16, 0, AUX);
+        }
+    };
+
+    const uint64_t* am = a.anc + (size_t)seg_r * FS_ANC_WORDS;
+    uint64_t mw0 = 0, mw1 = 0;
+    auto load_mask = [&](int tile) {
+        const int wd = min(max((tile * BS - l_glo) >> 6, 0), FS_ANC_WORDS - 1), wd1 = min(wd + 1, FS_ANC_WORDS - 1);
+        mw0 = am[wd];
+        mw1 = am[wd1];
+    };
+
+    // byte offsets of this lane's fragment reads inside a buffer (without the per-sub-tile strides)
+    unsigned kread[NKT], vread[NHT];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) kread[kt] = (unsigned)(r16 * ROWB + (((kt * 4 + g) ^ r16) * 16));
+    {
+        const int vr = g * 4 + (r16 >> 2);  // slot row & 15 of the transposing read
+#pragma unroll
+        for (int nt = 0; nt < NHT; ++nt) vread[nt] = (unsigned)(KBYTES + vr * ROWB + (((nt * 2 + ((r16 & 3) >> 1)) ^ vr) * 16) + (r16 & 1) * 8);
+    }
+
+    auto process = [&](int tile, const unsigned char* buf, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const int s0 = tile * BS;
+        if (!computes) return;
+        const bool need_mask = MASKED && (s0 + BS > l_glo);  // the tile touches draft slots or the tail beyond L
+        uint64_t vm = 0;
+        if (need_mask) {
+            const int d0 = s0 - l_glo, valid = L - s0;  // valid >= 1
+            uint64_t m;
+            if (d0 >= 0) {
+                const int wd = d0 >> 6, sh = d0 & 63;
+                m = mw0 >> sh;
+                if (sh && wd + 1 < FS_ANC_WORDS) m |= mw1 << (64 - sh);
+            } else {
+                m = ((1ull << (-d0)) - 1) | (mw0 << (-d0));  // 0 < -d0 < BS <= 64
+            }
+            if (valid < 64) m &= (1ull << valid) - 1;
+            if (!rok) m = 0;
+            vm = m >> (g * 4);
+            if (__ballot(m != 0) == 0) return;  // wave-uniform: none of the wave's rows sees a slot of this tile
+        }
+        // ---- S^T = K . Q^T ----
+        f32x4 st[BS / 16];
+#pragma unroll
+        for (int j = 0; j < BS / 16; ++j) {
+            st[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kt = 0; kt < NKT; ++kt) {
+                const frag_t kf = *(const frag_t*)(buf + kread[kt] + j * 16 * ROWB);
+                st[j] = E::mma(kf, qf[kt], st[j]);
+            }
+        }
+        // ---- mask, online softmax (as in tree_attn_kernel) ----
+        float mx = NEG_BIG;
+        if (need_mask) {
+#pragma unroll
+            for (int j = 0; j < BS / 16; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float sv = st[j][v] * a.scale_log2;
+                    const unsigned half = (j * 16 + v) < 32 ? (unsigned)vm : (unsigned)(vm >> 32);
+                    if (!(half & (1u << ((j * 16 + v) & 31)))) sv = NEG_BIG;
+                    st[j][v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < BS / 16; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx = fmaxf(mx, st[j][v]);
+            mx *= a.scale_log2;
+        }
+        mx = wave_xor_max(wave_xor_max(mx, 16), 32);
+        const float mnew = fmaxf(mrun, mx);
+        if (__ballot(mnew != mrun) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+            lrun *= alpha;
+#pragma unroll
+            for (int nt = 0; nt < NHT; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[nt][v] *= alpha;
+            mrun = mnew;
+        }
+        float psum = 0.f;
+        float p[BS / 16][4];
+        if (need_mask) {
+#pragma unroll
+            for (int j = 0; j < BS / 16; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float sv = st[j][v];
+                    const float e = (sv <= NEG_BIG) ? 0.f : __builtin_amdgcn_exp2f(sv - mnew);
+                    p[j][v] = e;
+                    psum += e;
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < BS / 16; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[j][v], a.scale_log2, -mnew));
+                    p[j][v] = e;
+                    psum += e;
+                }
+        }
+        lrun += psum;
+        frag_t pf[NPF];
+#pragma unroll
+        for (int jj = 0; jj < NPF; ++jj)
+#pragma unroll
+            for (int e = 0; e < EPF; ++e) pf[jj][e] = E::from_f(p[jj * NSUB + e / 4][e % 4]);
+        // ---- O^T += V^T . P^T (transposing LDS load, rows jj * 32 + g * 4 + (r16 >> 2) and + 16) ----
+#pragma unroll
+        for (int jj = 0; jj < NPF; ++jj)
+#pragma unroll
+            for (int nt = 0; nt < NHT; ++nt) {
+                const unsigned char* vp = buf + vread[nt] + jj * 32 * ROWB;
+                const s16x4 t0v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
+                const s16x4 t1v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 16 * ROWB));
+                const frag_t vf = __builtin_bit_cast(frag_t, __builtin_shufflevector(t0v, t1v, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc[nt] = E::mma(vf, pf[jj], acc[nt]);
+            }
+    };
+
+    using unmasked_t = std::integral_constant<bool, false>;
+    using masked_t = std::integral_constant<bool, true>;
+    if (t1 > t0) {  // uniform over the workgroup
+#pragma unroll
+        for (int k = 0; k + 1 < NBUF; ++k) issue(min(t0 + k, t1 - 1), buf_at(k));
+        FS_WAIT_VM_LGKM(LPT * (NBUF - 1), 15);  // the Q fragments (issued before the tiles) are there; the tiles stay in flight
+        // tile `tile` sits in buffer k.  The refill is never skipped (past the end it re-reads the range's last tile), so the
+        // loads in flight at every wait are counted exactly: all but the newest NBUF - 2 tiles' worth have landed.
+        auto step = [&](int tile, auto kc, auto masked_tag) {
+            constexpr int k = decltype(kc)::value;
+            constexpr bool MASKED = decltype(masked_tag)::value;
+            asm volatile("" ::: "memory");
+            FS_WAIT_VM_LGKM(LPT * (NBUF - 2), 0);
+            __builtin_amdgcn_s_barrier();  // tile `tile` complete for every wave; every wave is done with tile - 1
+            asm volatile("" ::: "memory");
+            if (MASKED) load_mask(tile);
+            issue(min(tile + NBUF - 1, t1 - 1), buf_at((k + NBUF - 1) % NBUF));
+            process(tile, buf_at(k), masked_tag);
+        };
+        using b0 = std::integral_constant<int, 0>;
+        using b1 = std::integral_constant<int, 1>;
+        using b2 = std::integral_constant<int, 2>;
+        using b3 = std::integral_constant<int, 3>;
+        // The tile range has an unmasked part (slots below l_glo: [t0, tA)) and a masked part ([tA, t1): draft slots and the tail
+        // beyond L); tA sits on a buffer-ring boundary, so the masked part may begin with tiles that need no mask.
+        const int t_mask = max(t0, min(t1, l_glo / BS));
+        const int tA = t0 + (t_mask - t0) / NBUF * NBUF;
+        int tile = t0;
+        for (; tile < tA; tile += NBUF) {
+            step(tile, b0{}, unmasked_t{});
+            step(tile + 1, b1{}, unmasked_t{});
+            if constexpr (NBUF >= 3) step(tile + 2, b2{}, unmasked_t{});
+            if constexpr (NBUF >= 4) step(tile + 3, b3{}, unmasked_t{});
+        }
+        for (; tile < t1; tile += NBUF) {  // the conditions are uniform over the workgroup
+            step(tile, b0{}, masked_t{});
+            if (tile + 1 < t1) step(tile + 1, b1{}, masked_t{});
+            if constexpr (NBUF >= 3)
+                if (tile + 2 < t1) step(tile + 2, b2{}, masked_t{});
+            if constexpr (NBUF >= 4)
+                if (tile + 3 < t1) step(tile + 3, b3{}, masked_t{});
+        }
+        // every direct-to-LDS load has landed before the workgroup's LDS is given back
+        FS_WAIT_VM_LGKM(0, 0);
+    }
+
+    // ---- write out (as tree_attn_kernel) ----
+    const float l = wave_xor_add(wave_xor_add(lrun, 16), 32);
+    if (!rok) return;
+    if (a.n_splits == 1) {
+        const float inv = 1.0f / l;
+        const int qh = kvh * a.G + rho / M;
+#pragma unroll
+        for (int nt = 0; nt < NHT; ++nt)
+            *(typename E::out4_t*)((T*)a.o + frag_major_index<T>(seg_r, qh * HD + nt * 16 + g * 4, a.Hq * HD / KT)) =
+                E::pack4(acc[nt][0] * inv, acc[nt][1] * inv, acc[nt][2] * inv, acc[nt][3] * inv);
+    } else {
+        const size_t prow = ((size_t)split * a.Hkv + kvh) * a.Rpad + a.G * row0 + rho;
+        float* po = a.part_o + prow * HD + g * 4;
+#pragma unroll
+        for (int nt = 0; nt < NHT; ++nt) *(f32x4*)(po + nt * 16) = acc[nt];
+        if (g == 0) *(float2*)(a.part_ml + prow * 2) = make_float2(mrun, l);
+    }
+}
+
 // Combine the splits: MERGE_LANES threads per (KV head, row, 4 head-dim elements).
 template <typename T, int MERGE_LANES>
 __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
@@ -451,8 +720,25 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
     if (ring > 2 && (sizeof(T) != 2 || nw != 4)) ring = 2;
     const bool deep = ring >= 2;
     bool done = false;
+    if constexpr (sizeof(T) == 2 && HD == 128) {
+        if (a.dma >= 2 && MTW == 1 && nw == 4) {
+            const bool stream = row_blocks == 1;
+            if (a.dma >= 4) {
+                if (stream) hipLaunchKernelGGL((tree_attn_dma_kernel<4, true>), grid, block, 0, s, row_blocks, a);
+                else hipLaunchKernelGGL((tree_attn_dma_kernel<4, false>), grid, block, 0, s, row_blocks, a);
+            } else if (a.dma == 3) {
+                if (stream) hipLaunchKernelGGL((tree_attn_dma_kernel<3, true>), grid, block, 0, s, row_blocks, a);
+                else hipLaunchKernelGGL((tree_attn_dma_kernel<3, false>), grid, block, 0, s, row_blocks, a);
+            } else {
+                if (stream) hipLaunchKernelGGL((tree_attn_dma_kernel<2, true>), grid, block, 0, s, row_blocks, a);
+                else hipLaunchKernelGGL((tree_attn_dma_kernel<2, false>), grid, block, 0, s, row_blocks, a);
+            }
+            done = true;
+        }
+    }
     if constexpr (sizeof(T) == 2) {
-        if (MTW == 1 && nw == 4 && ring >= 4) {
+        if (done) {
+        } else if (MTW == 1 && nw == 4 && ring >= 4) {
             hipLaunchKernelGGL((tree_attn_kernel<T, HD, 1, 4, 4, true>), grid, block, 0, s, row_blocks, a);
             done = true;
         } else if (MTW == 1 && nw == 4 && ring == 3) {
@@ -492,7 +778,7 @@ static hipError_t launch_hd(const AttnArgs& a, int MTW, int row_blocks, hipStrea
 }
 
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
-               int nwc_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset) {
+               int nwc_override, int dma_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset, int* dma) {
     const int R = G * M, mtiles = (R + 15) / 16;
     const int BS = attn_tile_slots(elem_bytes, hd);
     const int ntiles = (L + BS - 1) / BS;
@@ -521,7 +807,14 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
         mtw = 1;
         nw_cap = 4;
     }
-    if (mtw_override > 0) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
+    // the direct-to-LDS kernel: 16-bit K/V, head dim 128, at most 4 one-tile waves
+    const bool dma_shape = elem_bytes == 2 && hd == 128 && mtiles <= 4;
+    int dma_bufs = 0;
+    if (dma_override >= 2 && dma_shape) {
+        dma_bufs = dma_override > 4 ? 4 : dma_override;
+        mtw = 1;
+    }
+    if (mtw_override > 0 && !dma_bufs) mtw = (mtw_override >= 2 && mtiles > 1) ? 2 : 1;
     if (wgs_override > 0) target = wgs_override;
     if (nwc_override > 0) nw_cap = nwc_override < 8 ? nwc_override : 8;
     int nw = (mtiles + mtw - 1) / mtw;
@@ -546,6 +839,17 @@ void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_spl
     if (nset_override <= 0 && *tiles_per_split < 4) ring = 1;
     if (ring > *tiles_per_split) ring = *tiles_per_split;
     *nset = ring < 1 ? 1 : ring;
+    // The direct-to-LDS kernel where it measured faster: one workgroup per compute unit on a long context with three tile
+    // buffers (16k context, 64 rows: 54.6 -> 53.0 us with the merge; two or four buffers 56.7 / 55.2), and grids of two and more
+    // workgroups per compute unit with two buffers, two workgroups sharing a unit's LDS (16 / 24 / 32 stacked requests of a
+    // 1k context: 55.5 -> 49.9, 81.1 -> 78.0, 107.9 -> 99.0 us; three buffers: slower than the register ring).
+    if (dma_override == 0 && dma_shape && mtw == 1 && nw <= 4 && *tiles_per_split >= 6) {
+        if ((long long)per_split * *n_splits >= 512)
+            dma_bufs = 2;
+        else if (deep_ring)
+            dma_bufs = 3;
+    }
+    *dma = dma_bufs;
 }
 
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s) {

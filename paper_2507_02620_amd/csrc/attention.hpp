@@ -26,6 +26,7 @@ struct AttnArgs {
     float* part_ml;       // [n_splits][Hkv][Rpad][2]
     int nwc;              // compute waves per workgroup (workgroups have at least 4 waves for staging)
     int nset;             // tiles in flight per workgroup for long splits with one row tile per wave (2 .. 4; set by attn_plan)
+    int dma;              // >= 2: the direct-to-LDS kernel with that many tile buffers (bf16, head dim 128, one row tile per wave, <= 4 waves)
     AttnReq req[ATTN_MAX_REQ];  // last: the fields above stay within the first cache lines of the kernel-argument segment
 };
 
@@ -33,7 +34,8 @@ struct AttnArgs {
 static inline int attn_tile_slots(int elem_bytes, int hd) { return elem_bytes * hd >= 512 ? 32 : 64; }
 
 // wgs_override / mtw_override / nset_override > 0 replace the plan's own choice of the workgroup target, of the row tiles per wave and of
-// the K/V tiles in flight per workgroup (tuning knobs)
+// the K/V tiles in flight per workgroup (tuning knobs); dma_override: 0 = plan's choice, 1 = never the direct-to-LDS kernel, 2 .. 4 = that
+// kernel with so many tile buffers wherever its shape allows
 void attn_plan(int elem_bytes, int hd, int M, int G, int Hkv, int L, int max_splits, int wgs_override, int mtw_override, int nset_override,
-               int nwc_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset);
+               int nwc_override, int dma_override, int* NWC, int* MTW, int* row_blocks, int* n_splits, int* tiles_per_split, int* nset, int* dma);
 hipError_t launch_attention(int dtype, const AttnArgs& a, int MTW, int row_blocks, hipStream_t s);

@@ -91,5 +91,12 @@ struct IdxList {
     short v[1024];
 };
 
+// Direct-to-LDS loads (__builtin_amdgcn_global_load_lds) take address-space-qualified pointers; the LDS one is wave-uniform,
+// the hardware adds lane * 16.
+#define FS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define FS_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+// s_waitcnt immediate (gfx9 encoding): vmcnt = n (6 bits), lgkmcnt = l (4 bits: at most l LDS reads still in flight), expcnt untouched
+#define FS_WAIT_VM_LGKM(n, l) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 15) | (((n) >> 4) << 14) | ((l) << 8))
+
 static __device__ __forceinline__ float wave_xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, FS_WAVE)); }
 static __device__ __forceinline__ float wave_xor_add(float v, int mask) { return v + __shfl_xor(v, mask, FS_WAVE); }

@@ -644,10 +644,6 @@ __global__ void __launch_bounds__(256) wide_fixup_kernel(const GemmArgs a, int n
 //     done).  Behind the barrier stage kt + 1 is complete for every wave and the buffer of stage kt - 1 is free.
 //   * Epilogues, RMSNorm hand-over (partial sums of squares from the producer) and XCD-aware placement are those of the
 //     128-row kernel; K slices (PARTIAL) write the same raw tiles for the same fix-up kernel.
-#define FS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define FS_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-// s_waitcnt immediate (gfx9 encoding): vmcnt = n (6 bits), lgkmcnt = l (4 bits: at most l LDS reads still in flight), expcnt untouched
-#define FS_WAIT_VM_LGKM(n, l) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 15) | (((n) >> 4) << 14) | ((l) << 8))
 
 template <int EPI, bool PARTIAL, int WM, int WN, int MT, int NT, int STAGES>
 __global__ void __launch_bounds__(WM * WN * 64) block_gemm_kernel(const GemmArgs a, int layout_nt, int n_tiles, int n_cols, int m_blocks, int k_splits,

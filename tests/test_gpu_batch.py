@@ -51,6 +51,9 @@ def _run_batch(cfg, specs, seed, head=False, w4=False):
     # one KV head under 8 query heads, long contexts: row blocks of four one-tile waves; the shorter request has no third row block
     ("wide-group-long-context", synth.StageConfig("b-gqa", "bf16", 1, 1024, 8, 1, 128, 1408, 0, 0, 64, 16, 6, 3),
      [(2100, 40, 6, 3, 16, 20), (1500, 30, 5, 3, 16, 12)]),
+    # 16 requests x 32 KV heads = 512 attention workgroups of 7 K/V tiles each: the plan's direct-to-LDS kernel with two tile buffers
+    ("many-heads-direct-to-lds", synth.StageConfig("b-dma", "bf16", 1, 512, 32, 32, 128, 1408, 0, 0, 64, 16, 6, 3),
+     [(400 + 7 * i, 32, 5, 3, 16, 16) for i in range(16)]),
     ("f32", synth.StageConfig("b-f32", "f32", 1, 256, 4, 4, 64, 688, 0, 0, 64, 16, 5, 3),
      [(30, 24, 5, 3, 8, 8), (64, 16, 4, 2, 0, 16), (5, 40, 6, 3, 24, 16)]),
 ])

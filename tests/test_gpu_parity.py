@@ -106,6 +106,27 @@ def test_long_kv_splits_deeper_rings(name, cfg, seg, wgs, nset, monkeypatch):
     _check_stage(cfg.with_(name=name, seg_len=seg), 5, seg)
 
 
+@pytest.mark.parametrize("bufs", [2, 3, 4])
+@pytest.mark.parametrize("name,cfg,seg,wgs", [
+    # the tree-attention kernel that copies K/V tiles straight into LDS (2 to 4 tile buffers): one split of 13 tiles with a
+    # ragged tail, two splits, a split shorter than the buffer ring, 64-row segments (4 waves computing), a ragged 24-row
+    # segment (two of the waves compute), and a context so short that most tiles are draft slots
+    ("dma-13-tiles", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 4),
+    ("dma-two-splits", SMALL_BF16.with_(l_glo=790, tree_size=40), 16, 8),
+    ("dma-short-splits", SMALL_BF16.with_(l_glo=300, tree_size=40), 16, 16),
+    ("dma-seg64", SMALL_BF16.with_(l_glo=600, tree_size=128, max_depth=10), 64, 4),
+    ("dma-seg24-ragged", SMALL_BF16.with_(l_glo=333, tree_size=50), 24, 4),
+    ("dma-mostly-draft-slots", SMALL_BF16.with_(l_glo=8, tree_size=640, max_depth=14), 16, 4),
+    ("dma-gqa-row-blocks", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=500, tree_size=70), 16, 8),
+])
+def test_long_kv_splits_direct_to_lds(name, cfg, seg, wgs, bufs, monkeypatch):
+    if "row-blocks" in name:  # two one-tile waves per workgroup: the 64 stacked rows of a KV head make two row blocks
+        monkeypatch.setenv("FLOWSPEC_ATTN_NWC", "2")
+    monkeypatch.setenv("FLOWSPEC_ATTN_WGS", str(wgs))
+    monkeypatch.setenv("FLOWSPEC_ATTN_DMA", str(bufs))
+    _check_stage(cfg.with_(name=f"{name}-{bufs}", seg_len=seg), 5, seg)
+
+
 @pytest.mark.parametrize("name,cfg,seg,wgs", [
     # one case per tree-attention variant, each with a context so short (l_glo <= 16) that the draft slots — the part the
     # ancestor mask governs — carry most of the attention weight
@@ -117,6 +138,7 @@ def test_long_kv_splits_deeper_rings(name, cfg, seg, wgs, nset, monkeypatch):
     ("mask-gqa", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=12, tree_size=100, max_depth=10), 32, None),
     ("mask-gqa-row-blocks", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=3, tree_size=200, max_depth=10), 80, None),
     ("mask-gqa-four-wave-row-blocks", SMALL_BF16.with_(n_q_heads=8, n_kv_heads=2, d_model=1024, l_glo=12, tree_size=200, max_depth=10), 48, -4),
+    ("mask-direct-to-lds", SMALL_BF16.with_(l_glo=8, tree_size=300, max_depth=12), 16, -100),
 ])
 def test_bf16_comparison_would_notice_a_wrong_mask(name, cfg, seg, wgs, monkeypatch):
     """The bf16 tolerance is wide, so these cases show that the comparison still discriminates: the HIP path's distance
@@ -124,7 +146,10 @@ def test_bf16_comparison_would_notice_a_wrong_mask(name, cfg, seg, wgs, monkeypa
     depths (same positions) but other ancestors."""
     from tests.gpu_util import max_rel_err
     from tests.helpers import make_oracle_stage, reparent_same_depth, verify_whole_tree
-    if wgs and wgs < 0:  # at most -wgs one-tile waves per workgroup: row blocks of four-wave workgroups
+    if wgs == -100:  # the direct-to-LDS kernel, three tile buffers, long splits
+        monkeypatch.setenv("FLOWSPEC_ATTN_DMA", "3")
+        monkeypatch.setenv("FLOWSPEC_ATTN_WGS", "4")
+    elif wgs and wgs < 0:  # at most -wgs one-tile waves per workgroup: row blocks of four-wave workgroups
         monkeypatch.setenv("FLOWSPEC_ATTN_NWC", str(-wgs))
         monkeypatch.setenv("FLOWSPEC_ATTN_MTW", "1")
     elif wgs:
