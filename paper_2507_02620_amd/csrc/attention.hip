@@ -502,8 +502,11 @@ __global__ void __launch_bounds__(256) tree_attn_dma_kernel(int row_blocks, cons
         row_off[i] = (unsigned)(16 * w + r) * row_bytes;
         col_off[i] = (unsigned)(((lane & 15) ^ r) * 16);
     }
+    // A tile beyond the range (tile >= t1, uniform) is still "loaded", so that every step issues the same number of loads and
+    // the wait counts below are exact; its row offset is pushed to the clamp, so all its loads fetch the one last valid row
+    // (two cache lines) into a buffer nobody reads.
     auto issue = [&](int tile, unsigned char* buf) {
-        const unsigned t = (unsigned)(tile * BS) * row_bytes;
+        const unsigned t = tile < t1 ? (unsigned)(tile * BS) * row_bytes : last_row;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const unsigned off = min(row_off[i] + t, last_row) + col_off[i];
@@ -639,10 +642,10 @@ __global__ void __launch_bounds__(256) tree_attn_dma_kernel(int row_blocks, cons
     using masked_t = std::integral_constant<bool, true>;
     if (t1 > t0) {  // uniform over the workgroup
 #pragma unroll
-        for (int k = 0; k + 1 < NBUF; ++k) issue(min(t0 + k, t1 - 1), buf_at(k));
+        for (int k = 0; k + 1 < NBUF; ++k) issue(t0 + k, buf_at(k));
         FS_WAIT_VM_LGKM(LPT * (NBUF - 1), 15);  // the Q fragments (issued before the tiles) are there; the tiles stay in flight
-        // tile `tile` sits in buffer k.  The refill is never skipped (past the end it re-reads the range's last tile), so the
-        // loads in flight at every wait are counted exactly: all but the newest NBUF - 2 tiles' worth have landed.
+        // tile `tile` sits in buffer k.  Loads return in order and every step issues one tile's worth, so at each wait all
+        // but the newest NBUF - 2 tiles' worth have landed (mask loads issued in between only make a wait stricter).
         auto step = [&](int tile, auto kc, auto masked_tag) {
             constexpr int k = decltype(kc)::value;
             constexpr bool MASKED = decltype(masked_tag)::value;
@@ -651,7 +654,7 @@ __global__ void __launch_bounds__(256) tree_attn_dma_kernel(int row_blocks, cons
             __builtin_amdgcn_s_barrier();  // tile `tile` complete for every wave; every wave is done with tile - 1
             asm volatile("" ::: "memory");
             if (MASKED) load_mask(tile);
-            issue(min(tile + NBUF - 1, t1 - 1), buf_at((k + NBUF - 1) % NBUF));
+            issue(tile + NBUF - 1, buf_at((k + NBUF - 1) % NBUF));
             process(tile, buf_at(k), masked_tag);
         };
         using b0 = std::integral_constant<int, 0>;
