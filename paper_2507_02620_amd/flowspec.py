@@ -174,7 +174,8 @@ class Stage:
 
     def close(self):
         if getattr(self, "_handle", None):
-            _lib.fs_stage_destroy(self._handle)
+            if _lib is not None:  # at interpreter exit the module's globals may already be gone; the process frees the stage then
+                _lib.fs_stage_destroy(self._handle)
             self._handle = None
 
     def __del__(self):
