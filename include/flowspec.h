@@ -269,7 +269,7 @@ int fs_accept_result_to_host(const fs_accept_result *res_dev, const int32_t *ret
                              int32_t *retain_host, void *stream);
 
 /*
- * KV-cache pruning (Sec. III-C, "KV cache pruning"): with I_incache = { i in I_retain : l_glo + i < l_cache },
+ * KV-cache pruning (Sec. III-C, the paragraph on pruning the KV cache): with I_incache = { i in I_retain : l_glo + i < l_cache },
  * slot l_glo + j <- slot l_glo + I_incache[j] for every layer, K and V, every head; slots below l_glo are not
  * touched.  Bit-exact copy, in place.
  *   retain / res   either both device (straight from fs_tree_accept; counts are read on the device), or
@@ -282,7 +282,7 @@ int fs_kv_compact(fs_stage *stage, fs_kv_cache kv, int l_glo, int l_cache, const
                   int n_retain_host, int n_acc_host, int32_t *new_len, void *stream);
 
 /*
- * Draft-segment pruning (Sec. III-C, "Draft segment pruning"): the in-flight segment holds S indices
+ * Draft-segment pruning (Sec. III-C, the paragraph on pruning draft segments): the in-flight segment holds S indices
  * [off, off + l_s) with off = l_cache - l_glo; rows with off + r in I_retain are gathered, in order, into
  * seg_out (must not overlap seg_in); *l_s_out = number kept.
  *   seg_in / seg_out device [l_s, row_bytes]; row_bytes a multiple of 4

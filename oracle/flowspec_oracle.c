@@ -9,8 +9,8 @@
  *
  * What it computes (paper, Sec. III):
  *   - orc_tree_ancestors : tree attention mask + tree position ids of a draft
- *     sequence S in descending-score order (Sec. III-A "tree position IDs and
- *     attention mask"; Sec. III-B: S is a topological order).
+ *     sequence S in descending-score order (Sec. III-A: a segment's position IDs and
+ *     attention mask follow the tree; Sec. III-B: S is a topological order).
  *   - orc_verify_stage   : forward of a block of decoder layers (Appendix A:
  *     self-attention, FFN, residuals; LLaMA2/Qwen2 form) over one draft segment
  *     with the tree mask, appending the segment's K/V to the stage cache.
