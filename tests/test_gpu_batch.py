@@ -117,3 +117,43 @@ def test_batch_errors():
     with pytest.raises(fs.FlowSpecError) as e:
         pair.gpu.tree_verify_batch([ok, (other, 0, 0, 0, 4, par)], hid)
     assert e.value.code == fs.FS_EINVAL
+
+
+def _random_batch(i):
+    r = np.random.default_rng(9100 + i)
+    hd = int(r.choice([64, 128]))
+    n_kv = int(r.choice([1, 2, 4]))
+    n_q = n_kv * int(r.choice([1, 2, 4]))
+    dtype = "f32" if i % 3 == 2 else "bf16"
+    kt = 16 if dtype == "f32" else 32
+    cfg = synth.StageConfig(f"b-rnd{i}", dtype, int(r.integers(1, 3)), int(r.integers(6, 20)) * kt, n_q, n_kv, hd, int(r.integers(10, 40)) * kt,
+                            0, 0, 64, 16, 6, 3, qkv_bias=bool(i % 2))
+    specs = []
+    for _ in range(int(r.integers(2, 7))):
+        T = int(r.integers(2, 90))
+        seg_off = int(r.integers(0, T))
+        specs.append((int(r.choice([0, 3, int(r.integers(4, 900))])), T, int(r.integers(2, 12)), int(r.choice([0, 2, 3])), seg_off,
+                      int(r.integers(1, min(40, T - seg_off) + 1))))
+    return cfg, specs
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_random_batches(i):
+    """Seeded random batches: 2 to 6 requests of unrelated context lengths, tree sizes, segment offsets and segment lengths."""
+    from tests.gpu_util import TOL, max_rel_err
+    cfg, specs = _random_batch(i)
+    print(f"[case] random batch {i}: {cfg.dtype} heads {cfg.n_q_heads}/{cfg.n_kv_heads} x {cfg.head_dim}, specs {specs}", flush=True)
+    cfg = cfg.with_(l_glo=max(s[0] for s in specs), tree_size=max(s[1] for s in specs))
+    # the rows before a request's segment are verified in one call of their own: the stage must take that many rows too
+    got, want, caches, cfg = _run_batch(cfg.with_(seg_len=max(64, sum(s[5] for s in specs), max(s[4] for s in specs))), specs, seed=40 + i)
+    row = 0
+    for rq, w in enumerate(want):
+        n = w.shape[0]
+        err = max_rel_err(got[row:row + n], w)
+        print(f"  request {rq}: {n} rows, hidden max-rel-err {err:.3e}", flush=True)
+        assert err < TOL[cfg.dtype]
+        row += n
+    for kv, orc, l_glo, seg_off, l_s in caches:
+        for l in range(cfg.n_layers):
+            g = kv[l][:, :, l_glo + seg_off:l_glo + seg_off + l_s].float().cpu().numpy()
+            assert max_rel_err(g, orc.kv[l][:, :, l_glo + seg_off:l_glo + seg_off + l_s]) < TOL[cfg.dtype]
