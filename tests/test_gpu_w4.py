@@ -91,3 +91,42 @@ def test_w4_rejects_f32_and_bad_shapes():
     with pytest.raises(fs.FlowSpecError):
         fs.Stage(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=512, vocab=0, dtype=fs.FS_F32, rms_eps=1e-5,
                  rope_theta=1e4, kv_capacity=64, max_tree=16, max_seg=16, layers=[], weight_format=fs.FS_WFMT_INT4_G128)
+
+
+def _random_w4(i):
+    r = np.random.default_rng(8200 + i)
+    hd = int(r.choice([64, 128]))
+    n_kv = int(r.choice([1, 2, 4]))
+    n_q = n_kv * int(r.choice([1, 2, 4]))
+    while (n_q * hd) % 128:   # one scale per 128 input columns of the attention output projection
+        n_q += n_kv
+    return synth.StageConfig(f"w4-rnd{i}", "bf16", int(r.integers(1, 3)), int(r.integers(2, 8)) * 128, n_q, n_kv, hd, int(r.integers(3, 12)) * 128,
+                             int(r.choice([0, 777, 2000])), int(r.choice([0, 5, int(r.integers(6, 1200))])), int(r.integers(2, 120)),
+                             int(r.integers(1, 66)), int(r.integers(2, 20)), int(r.choice([0, 2, 4])), qkv_bias=bool(i % 2))
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_w4_random_shapes(i):
+    """Seeded random 4-bit stages (widths in multiples of the 128-column scale group, ragged trees and segments, with and
+    without head): hidden states, appended K/V and logits against the oracle."""
+    import torch
+    from tests.gpu_util import TOL, Pair, max_rel_err, to_dev
+    cfg = _random_w4(i)
+    print(f"[case] {cfg}", flush=True)
+    pair = Pair(cfg, seed=60 + i, head=cfg.vocab > 0, w4=True)
+    tree = synth.config_tree(cfg, seed=60 + i)
+    hid = synth.hidden(cfg, tree.size, 0, 60 + i)
+    o, g = pair.verify_tree(tree.parent, hid, cfg.seg_len)
+    err = max_rel_err(g, o)
+    L = cfg.l_glo + tree.size
+    kerr = max_rel_err(pair.kv[:, :, :, cfg.l_glo:L].float().cpu().numpy(), pair.orc.kv[:, :, :, cfg.l_glo:L])
+    print(f"  hidden max-rel-err {err:.3e}, appended K/V {kerr:.3e}", flush=True)
+    assert err < TOL["bf16"] and kerr < TOL["bf16"]
+    if cfg.vocab:
+        n = min(cfg.seg_len, tree.size)
+        rows = synth.storage(cfg, o[:n].astype(np.float32))
+        lo, _ = pair.orc.logits(rows.astype(np.float64))
+        lg, _ = pair.gpu.tree_logits(to_dev(rows, torch.bfloat16))
+        lerr = max_rel_err(lg.float().cpu().numpy(), lo)
+        print(f"  logits max-rel-err {lerr:.3e}", flush=True)
+        assert lerr < TOL["bf16"]
