@@ -907,10 +907,10 @@ static hipError_t launch_block(int layout_nt, int n_tiles, const GemmArgs& a, hi
     return hipGetLastError();
 }
 
-// Which of the two many-row kernels takes a projection.  A compute unit pulls in about 50 GB/s in either kernel (a fifth of
-// the requests go beyond the XCD's L2 and a request takes 400 cycles and more on average), so both kernels are bound by
-// bytes per block: the 256-row block needs two thirds of the 128-row blocks' bytes per flop, but the compute units take its
-// blocks one at a time.  It wins when all its blocks run at once on most of the chip while the 128-row kernel would have to
+// Which of the two many-row kernels takes a projection.  The 256-row block needs two thirds of the 128-row blocks' operand
+// bytes per flop (a compute unit draws about 50 GB/s in either kernel; a fifth of the requests go beyond the XCD's L2 and a
+// request takes 400 cycles and more on average), but the compute units take its blocks one at a time, so a launch costs whole
+// rounds of blocks.  It wins when all its blocks run at once on most of the chip while the 128-row kernel would have to
 // give some compute units a second pair of blocks (measured, 1024 rows: QKV 111 -> 97 us; 512 rows: gate/up 108 -> 92 us);
 // with more than 256 blocks its second round costs more than it saves (1024 rows: gate/up 159 -> 187 us), with few blocks the
 // 128-row kernel's finer grain fills more compute units (512 rows: QKV 66 -> 92 us), and the K slices of the d_model-wide
