@@ -898,29 +898,38 @@ static hipError_t launch_wide_shape(int layout_nt, int n_tiles, const GemmArgs& 
     return hipGetLastError();
 }
 
-// 256-row blocks of 256 features, both operands through LDS (block_gemm_kernel).
-template <int EPI>
+// 256-row blocks of 256 or 192 features, both operands through LDS (block_gemm_kernel): 2 x 4 waves of 8 x 4 accumulator tiles, or
+// 4 x 2 waves of 4 x 6.
+template <int EPI, int WM, int WN, int MT, int NT>
 static hipError_t launch_block(int layout_nt, int n_tiles, const GemmArgs& a, hipStream_t s) {
-    const int n_cols = (n_tiles + 15) / 16, m_blocks = (a.M + 255) / 256;
+    constexpr int BNT = WN * NT;
+    const int n_cols = (n_tiles + BNT - 1) / BNT, m_blocks = (a.M + 255) / 256;
     const int grid = (n_cols + 7) / 8 * 8 * m_blocks;
-    hipLaunchKernelGGL((block_gemm_kernel<EPI, false, 2, 4, 8, 4, 4>), dim3(grid), dim3(512), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1, nullptr);
+    hipLaunchKernelGGL((block_gemm_kernel<EPI, false, WM, WN, MT, NT, 4>), dim3(grid), dim3(WM * WN * 64), 0, s, a, layout_nt, n_tiles, n_cols, m_blocks, 1,
+                       nullptr);
     return hipGetLastError();
 }
 
-// Which of the two many-row kernels takes a projection.  The 256-row block needs two thirds of the 128-row blocks' operand
-// bytes per flop (a compute unit draws about 50 GB/s in either kernel; a fifth of the requests go beyond the XCD's L2 and a
-// request takes 400 cycles and more on average), but the compute units take its blocks one at a time, so a launch costs whole
-// rounds of blocks.  It wins when all its blocks run at once on most of the chip while the 128-row kernel would have to
-// give some compute units a second pair of blocks (measured, 1024 rows: QKV 111 -> 97 us; 512 rows: gate/up 108 -> 92 us);
-// with more than 256 blocks its second round costs more than it saves (1024 rows: gate/up 159 -> 187 us), with few blocks the
-// 128-row kernel's finer grain fills more compute units (512 rows: QKV 66 -> 92 us), and the K slices of the d_model-wide
-// residual projections do no better either (1024 rows: 51 -> 58 us, 95 -> 96 us).
-static bool use_block_gemm(int mode, int epi, int M, int n_tiles) {  // mode 0 / 1: never / whenever possible (tuning knob); else the rule below
-    if (epi == EPI_RESID || mode == 0) return false;
-    if (mode == 1) return true;
-    const int cols = (n_tiles + 15) / 16;
-    const int blocks256 = cols * ((M + 255) / 256), blocks128 = cols * ((M + 127) / 128);
-    return blocks256 >= 144 && blocks256 <= 256 && blocks128 > 256;
+// Which many-row kernel takes a projection: 0 = the 128-row kernel, 16 / 12 = the 256-row kernel with blocks of 16 / 12 feature
+// tiles.  The 256-row block needs two thirds of the 128-row blocks' operand bytes per flop (a compute unit draws about 50 GB/s in
+// either kernel; a fifth of the requests go beyond the XCD's L2 and a request takes 400 cycles and more on average), but the
+// compute units take its blocks one at a time, so a launch costs whole rounds of blocks and what counts is how many of the 256
+// units its one round keeps busy: the width whose blocks number at most 256 and come closest to it (1024 rows x 12288 features:
+// 192 blocks of 256 features or 256 blocks of 192).  It wins when that is most of the chip while the 128-row kernel would have to
+// give some compute units a second pair of blocks (measured, 1024 rows: QKV 111 -> 97 us; 512 rows: gate/up 108 -> 92 us); with
+// more than 256 blocks its second round costs more than it saves (1024 rows: gate/up 159 -> 187 us), with few blocks the 128-row
+// kernel's finer grain fills more compute units (512 rows: QKV 66 -> 92 us), and the K slices of the d_model-wide residual
+// projections do no better either (1024 rows: 51 -> 58 us, 95 -> 96 us).
+static int block_gemm_width(int mode, int epi, int M, int n_tiles) {  // mode 0 / 1 / 2: never / always 16 tiles / always 12 tiles (tuning knob)
+    if (epi == EPI_RESID || mode == 0) return 0;
+    if (mode == 1) return 16;
+    if (mode == 2) return 12;
+    const int m_blocks = (M + 255) / 256;
+    const int b16 = (n_tiles + 15) / 16 * m_blocks, b12 = (n_tiles + 11) / 12 * m_blocks, blocks128 = (n_tiles + 15) / 16 * ((M + 127) / 128);
+    if (blocks128 <= 256) return 0;
+    if (b12 <= 256 && b12 >= 144) return 12;  // the narrower block has more blocks: closer to one per compute unit
+    if (b16 <= 256 && b16 >= 144) return 16;
+    return 0;
 }
 
 hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs& a, float* part, size_t part_bytes, int block_mode, hipStream_t s) {
@@ -930,11 +939,18 @@ hipError_t launch_gemm_wide(int epi, int layout_nt, int n_tiles, const GemmArgs&
         return hipErrorInvalidValue;
     const WideShape sh = wide_shape(epi, a.M);
     const bool narrow = sh.wnt == 2, half = sh.bmt == 4;
-    if (!narrow && !half && use_block_gemm(block_mode, epi, a.M, n_tiles)) {
+    const int bw = (!narrow && !half) ? block_gemm_width(block_mode, epi, a.M, n_tiles) : 0;
+    if (bw == 16) {
         switch (epi) {
-            case EPI_QKV: return launch_block<EPI_QKV>(layout_nt, n_tiles, a, s);
-            case EPI_SWIGLU: return launch_block<EPI_SWIGLU>(layout_nt, n_tiles, a, s);
-            case EPI_LOGITS: return launch_block<EPI_LOGITS>(layout_nt, n_tiles, a, s);
+            case EPI_QKV: return launch_block<EPI_QKV, 2, 4, 8, 4>(layout_nt, n_tiles, a, s);
+            case EPI_SWIGLU: return launch_block<EPI_SWIGLU, 2, 4, 8, 4>(layout_nt, n_tiles, a, s);
+            case EPI_LOGITS: return launch_block<EPI_LOGITS, 2, 4, 8, 4>(layout_nt, n_tiles, a, s);
+        }
+    } else if (bw == 12) {
+        switch (epi) {
+            case EPI_QKV: return launch_block<EPI_QKV, 4, 2, 4, 6>(layout_nt, n_tiles, a, s);
+            case EPI_SWIGLU: return launch_block<EPI_SWIGLU, 4, 2, 4, 6>(layout_nt, n_tiles, a, s);
+            case EPI_LOGITS: return launch_block<EPI_LOGITS, 4, 2, 4, 6>(layout_nt, n_tiles, a, s);
         }
     }
     switch (epi) {

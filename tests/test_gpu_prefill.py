@@ -45,15 +45,16 @@ def test_chain_segment(cfg, rows):
 @pytest.mark.parametrize("cfg,rows,head", [
     # the 256-row projection kernel (both operands through LDS) forced on for every normed projection: QKV with bias and
     # rotation, gate/up and the LM head, with row counts that leave the last 256-row block partly filled and feature counts
-    # that leave the last 256-feature block partly filled
+    # that leave the last 256-feature (or 192-feature) block partly filled
     (synth.StageConfig("blk-bf16-gqa-400", "bf16", 2, 512, 8, 2, 64, 1408, 1000, 90, 400, 400, 400, 1, qkv_bias=True), 400, True),
     (synth.StageConfig("blk-bf16-mha128-640", "bf16", 1, 1024, 8, 8, 128, 2816, 0, 77, 640, 640, 640, 1), 640, False),
     (synth.StageConfig("blk-bf16-1024", "bf16", 1, 512, 4, 4, 128, 1024, 0, 0, 1024, 1024, 1024, 1), 1024, False),
 ])
-def test_chain_segment_through_the_256_row_kernel(cfg, rows, head, monkeypatch):
+@pytest.mark.parametrize("width", [1, 2])   # knob values: blocks of 256 features (16 tiles) / of 192 features (12 tiles)
+def test_chain_segment_through_the_256_row_kernel(cfg, rows, head, width, monkeypatch):
     from tests.gpu_util import TOL, Pair, max_rel_err
-    monkeypatch.setenv("FLOWSPEC_BLOCK_GEMM", "1")
-    print(f"[case] {cfg.name} rows={rows}", flush=True)
+    monkeypatch.setenv("FLOWSPEC_BLOCK_GEMM", str(width))
+    print(f"[case] {cfg.name} rows={rows} block width knob {width}", flush=True)
     pair = Pair(cfg, seed=5, head=head)
     hid = synth.hidden(cfg, rows, 0, 5)
     o, g = pair.verify_tree(_chain(rows), hid, rows)
