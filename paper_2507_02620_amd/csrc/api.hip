@@ -258,7 +258,7 @@ struct Tunables {
         wide_rows = env_int("FLOWSPEC_WIDE_ROWS", 65); // stacked rows from which every projection takes the many-row kernel
         mid_rows = env_int("FLOWSPEC_MID_ROWS", 17);   // ... from which the wide projections do
         compact_cb = env_int("FLOWSPEC_COMPACT_CB", 0);  // KV compaction: column blocks per row (0: by the grid size)
-        block_gemm = env_int("FLOWSPEC_BLOCK_GEMM", -1);  // 256-row projection kernel: 0 never, 1 whenever possible, else by rule
+        block_gemm = env_int("FLOWSPEC_BLOCK_GEMM", -1);  // 256-row projection kernel: 0 never, 1 / 2 always (256- / 192-feature blocks), else by rule
     }
 };
 
